@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the Markovian next-scale attention hot path on one MI355X.
+
+A step is one forward plus one backward of the whole path over one batch of the 256px
+large-model training shape (10 scales, L = 680, B = 32, H = 24, D = 64, bf16).  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  value      useful TFLOP/s, fwd+bwd: (4 + 10) * D * A * B * H flops per step, A = number of
+             unmasked (query, key) pairs per head; element-exact, independent of tile sizes
+  roofline   the kernel with the largest share of the step, against the roof that bounds it
+  cpu_baseline  the fp64 oracle timed on the host cores on a sample of heads of the same shape
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2516.6      # MI355X dense bf16: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+WORKLOAD = "256px_b32_h24"
+METRIC = "useful TFLOP/s fwd+bwd (680 tok, H=24, D=64) and % of bf16 MFMA peak"
+
+
+def kernel_models(n_heads: int, L: int, D: int, A: int):
+    """Algorithmic bytes and useful flops of one launch of each kernel (inputs read once,
+    outputs written once; re-reads served by cache are not counted)."""
+    row = D * 2                                  # one bf16 row
+    rows = n_heads * L
+    pair_flops = 2 * D * A * n_heads             # one contraction over all unmasked pairs
+    return {
+        "hmar_fwd_kernel": {"bytes": rows * (4 * row + 4), "flops": 2 * pair_flops},
+        "hmar_delta_kernel": {"bytes": rows * (2 * row + 4), "flops": 0},
+        "hmar_dkdv_kernel": {"bytes": rows * (6 * row + 8), "flops": 4 * pair_flops},
+        "hmar_dq_kernel": {"bytes": rows * (5 * row + 8), "flops": 3 * pair_flops},
+    }
+
+
+def read_traffic(kernel: str):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    kept as `kernel = bytes` lines in profiles/hbm_traffic_<workload>.txt; None if absent."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{WORKLOAD}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.strip().startswith("#") or "=" not in line:
+                    continue
+                k, v = line.split("=", 1)
+                if k.strip() == kernel:
+                    return float(v.split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, A: int, budget_s: float = 15.0):
+    """Time the oracle (as it stands) on a bounded sample of heads of the same workload."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import hmar_attn_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    heads = 8
+    Q, K, V, dO = (si.to_f64(t) for t in si.make_inputs(w, heads=heads))
+
+    def run():
+        orc.attn_fwd(Q, K, V, w.sides)
+        orc.attn_bwd(Q, K, V, dO, w.sides)
+
+    run()                                         # warm-up (BLAS threads, page faults)
+    t0 = time.perf_counter()
+    run()
+    once = time.perf_counter() - t0
+    reps = max(1, min(50, int(budget_s / max(once, 1e-3))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    dt = (time.perf_counter() - t0) / reps
+    flops = 14 * w.D * A * heads
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{heads} of {w.B * w.H} heads of {w.name} (fp64 dense masked fwd+bwd), "
+                      f"{reps} repetitions, {dt:.3f} s each",
+            "seconds_per_head": dt / heads}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path shards over (batch, head) without communication; "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2506_04421_amd as hm
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("no GPU visible: this benchmark has no CPU path", file=sys.stderr)
+        return 3
+    w = si.WORKLOADS[WORKLOAD]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    offs, A = hm.hmar_schedule_describe(w.sides)
+    n_heads = w.B * w.H
+
+    # three rotating buffer sets (3 x 0.54 GB): no step finds its operands in the 256 MB
+    # last-level cache from the previous step
+    host = si.make_inputs(w)
+    sets = []
+    for i in range(3):
+        q, k, v, g = (torch.roll(t, shifts=i, dims=0).contiguous().to(dev) for t in host)
+        sets.append(dict(q=q, k=k, v=v, g=g, o=torch.empty_like(q),
+                         lse=torch.empty((w.B, w.H, w.L), dtype=torch.float32, device=dev),
+                         dq=torch.empty_like(q), dk=torch.empty_like(q), dv=torch.empty_like(q)))
+    del host
+    ws = torch.empty(hm.hmar_attn_bwd_workspace_bytes(w.sides, w.B, w.H, w.D), dtype=torch.uint8, device=dev)
+
+    def fwd(s):
+        hm.hmar_attn_fwd(s["q"], s["k"], s["v"], w.sides, 0.0, O=s["o"], LSE=s["lse"])
+
+    def bwd(s):
+        hm.hmar_attn_bwd(s["q"], s["k"], s["v"], s["o"], s["g"], s["lse"], w.sides, 0.0,
+                         dQ=s["dq"], dK=s["dk"], dV=s["dv"], workspace=ws)
+
+    def step(i):
+        s = sets[i % len(sets)]
+        fwd(s)
+        bwd(s)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # forward and backward separately, HIP events on the launch stream
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            fn(sets[i % len(sets)])
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+    fwd_ms = timed(fwd)
+    bwd_ms = timed(bwd)
+
+    # per-kernel durations: the same steps again with every launch bracketed by HIP events
+    hm.hmar_profile_begin()
+    for i in range(args.steps):
+        step(i)
+    prof = hm.hmar_profile_end()
+    kern_ms = {k: (ms / n if n else 0.0) for k, (ms, n) in prof.items()}
+    models = kernel_models(n_heads, w.L, w.D, A)
+    dominant = max(kern_ms, key=lambda k: kern_ms[k])
+    m = models[dominant]
+    t_dom = kern_ms[dominant] * 1e-3
+    hbm_time = m["bytes"] / (HBM_PEAK_GBS * 1e9)
+    mfma_time = m["flops"] / (MFMA_PEAK_TFLOPS * 1e12)
+    if hbm_time >= mfma_time:
+        achieved = m["bytes"] / t_dom / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS}
+    else:
+        achieved = m["flops"] / t_dom / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_PEAK_TFLOPS}
+    roof["traffic"] = read_traffic(dominant)
+    roof["kernel"] = dominant
+    roof["kernel_ms"] = kern_ms[dominant]
+    roof["algorithmic_bytes"] = m["bytes"]
+    roof["useful_flops"] = m["flops"]
+    roof["mfma_frac"] = m["flops"] / t_dom / 1e12 / MFMA_PEAK_TFLOPS
+    roof["hbm_frac"] = m["bytes"] / t_dom / 1e9 / HBM_PEAK_GBS
+
+    flops_fwd = 4 * w.D * A * n_heads
+    flops_bwd = 10 * w.D * A * n_heads
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+    step_bytes = n_heads * w.L * ((4 * 128 + 4) + (8 * 128 + 4 + 8))   # compulsory fwd + bwd
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: sides {list(w.sides)}, L={w.L}, B={w.B}, H={w.H}, D={w.D}, "
+                               f"Markovian mask, fwd+bwd, iid N(0,1) bf16 seed {w.seed}",
+                   "allowed_pairs_per_head": A, "buffer_sets": len(sets)},
+        "pct_mfma_peak": 100.0 * value / MFMA_PEAK_TFLOPS,
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "fwd_tflops": flops_fwd / (fwd_ms * 1e-3) / 1e12, "bwd_tflops": flops_bwd / (bwd_ms * 1e-3) / 1e12,
+        "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_ms": kern_ms,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, A)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

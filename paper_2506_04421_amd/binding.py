@@ -1,0 +1,183 @@
+"""ctypes binding of libhmar_attn.so: argument marshalling only.
+
+Every step of the path (tile schedule, forward, backward) runs inside the library; this
+module turns torch tensors into device pointers and a stream handle, checks dtypes and
+shapes, and raises on a non-zero status.  There is no fallback: if the library has not
+been built, importing the entry points fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhmar_attn.so")
+
+HMAR_OK = 0
+_lib = None
+
+
+class HmarError(RuntimeError):
+    pass
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen the in-tree library (once) and declare the C signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise HmarError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2506_04421_amd.build` "
+            "(there is no CPU or PyTorch fallback for this path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32, i64, f32, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+    pi32 = ctypes.POINTER(i32)
+    lib.hmar_status_string.restype = ctypes.c_char_p
+    lib.hmar_status_string.argtypes = [ctypes.c_int]
+    lib.hmar_attn_fwd.restype = ctypes.c_int
+    lib.hmar_attn_fwd.argtypes = [vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, f32, vp]
+    lib.hmar_attn_bwd_workspace_bytes.restype = sz
+    lib.hmar_attn_bwd_workspace_bytes.argtypes = [pi32, i32, i32, i32, i32]
+    lib.hmar_attn_bwd.restype = ctypes.c_int
+    lib.hmar_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, f32, vp, sz, vp]
+    lib.hmar_schedule_describe.restype = ctypes.c_int
+    lib.hmar_schedule_describe.argtypes = [pi32, i32, pi32, ctypes.POINTER(i64)]
+    lib.hmar_schedule_tiles.restype = ctypes.c_int
+    lib.hmar_schedule_tiles.argtypes = [pi32, i32, i32, pi32, i32, pi32, pi32, pi32]
+    lib.hmar_profile_begin.restype = ctypes.c_int
+    lib.hmar_profile_begin.argtypes = []
+    lib.hmar_profile_end.restype = ctypes.c_int
+    lib.hmar_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().hmar_status_string(int(code)).decode()
+
+
+def _check(code: int, what: str) -> None:
+    if code != HMAR_OK:
+        raise HmarError(f"{what} failed: {status_string(code)}")
+
+
+def _sides_array(side_lens: Sequence[int]):
+    sides = [int(s) for s in side_lens]
+    return (ctypes.c_int32 * len(sides))(*sides), len(sides)
+
+
+def _bf16_4d(name: str, t: torch.Tensor, shape=None):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise HmarError(f"{name} must be a device tensor")
+    if t.dtype != torch.bfloat16 or t.dim() != 4 or not t.is_contiguous():
+        raise HmarError(f"{name} must be a contiguous bf16 tensor of shape [B, H, L, D]")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise HmarError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t
+
+
+def _stream_handle(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def hmar_schedule_describe(side_lens: Sequence[int]) -> Tuple[list, int]:
+    """(prefix sums off[0..K], allowed (query, key) pairs per head); host only."""
+    lib = load_library()
+    arr, n = _sides_array(side_lens)
+    offs = (ctypes.c_int32 * (n + 1))()
+    pairs = ctypes.c_int64(0)
+    _check(lib.hmar_schedule_describe(arr, n, offs, ctypes.byref(pairs)), "hmar_schedule_describe")
+    return list(offs), int(pairs.value)
+
+
+def hmar_schedule_tiles(side_lens: Sequence[int], which: int):
+    """(items [(own_begin, own_end, other_begin, other_end)], row_lo, row_hi); host only."""
+    lib = load_library()
+    arr, n = _sides_array(side_lens)
+    L = sum(int(s) * int(s) for s in side_lens)
+    cnt = ctypes.c_int32(0)
+    _check(lib.hmar_schedule_tiles(arr, n, which, None, 0, ctypes.byref(cnt), None, None), "hmar_schedule_tiles")
+    items = (ctypes.c_int32 * (4 * cnt.value))()
+    lo = (ctypes.c_int32 * L)()
+    hi = (ctypes.c_int32 * L)()
+    _check(lib.hmar_schedule_tiles(arr, n, which, items, cnt.value, ctypes.byref(cnt), lo, hi), "hmar_schedule_tiles")
+    flat = list(items)
+    return [tuple(flat[4 * i:4 * i + 4]) for i in range(cnt.value)], list(lo), list(hi)
+
+
+def hmar_attn_fwd(Q, K, V, side_lens, sm_scale: float = 0.0, O=None, LSE=None):
+    """Forward on the tensors' device and current stream.  Returns (O bf16, LSE fp32)."""
+    lib = load_library()
+    _bf16_4d("Q", Q)
+    B, H, L, D = Q.shape
+    _bf16_4d("K", K, Q.shape)
+    _bf16_4d("V", V, Q.shape)
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, H, L), dtype=torch.float32, device=Q.device)
+    _bf16_4d("O", O, Q.shape)
+    if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, L) or not LSE.is_contiguous():
+        raise HmarError("LSE must be a contiguous fp32 tensor of shape [B, H, L]")
+    arr, n = _sides_array(side_lens)
+    if sum(int(s) * int(s) for s in side_lens) != L:
+        raise HmarError("sequence length does not match the scale schedule")
+    with torch.cuda.device(Q.device):
+        code = lib.hmar_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                                 arr, n, B, H, D, float(sm_scale), _stream_handle(Q))
+    _check(code, "hmar_attn_fwd")
+    return O, LSE
+
+
+def hmar_attn_bwd_workspace_bytes(side_lens, B: int, H: int, D: int) -> int:
+    lib = load_library()
+    arr, n = _sides_array(side_lens)
+    return int(lib.hmar_attn_bwd_workspace_bytes(arr, n, B, H, D))
+
+
+def hmar_attn_bwd(Q, K, V, O, dO, LSE, side_lens, sm_scale: float = 0.0,
+                  dQ=None, dK=None, dV=None, workspace=None):
+    """Backward on the tensors' device and current stream.  Returns (dQ, dK, dV) bf16."""
+    lib = load_library()
+    _bf16_4d("Q", Q)
+    B, H, L, D = Q.shape
+    for name, t in (("K", K), ("V", V), ("O", O), ("dO", dO)):
+        _bf16_4d(name, t, Q.shape)
+    if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, L) or not LSE.is_contiguous() or not LSE.is_cuda:
+        raise HmarError("LSE must be a contiguous device fp32 tensor of shape [B, H, L]")
+    dQ = torch.empty_like(Q) if dQ is None else _bf16_4d("dQ", dQ, Q.shape)
+    dK = torch.empty_like(Q) if dK is None else _bf16_4d("dK", dK, Q.shape)
+    dV = torch.empty_like(Q) if dV is None else _bf16_4d("dV", dV, Q.shape)
+    arr, n = _sides_array(side_lens)
+    if sum(int(s) * int(s) for s in side_lens) != L:
+        raise HmarError("sequence length does not match the scale schedule")
+    need = int(lib.hmar_attn_bwd_workspace_bytes(arr, n, B, H, D))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(Q.device):
+        code = lib.hmar_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+                                 LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                 arr, n, B, H, D, float(sm_scale), workspace.data_ptr(), ws_bytes,
+                                 _stream_handle(Q))
+    _check(code, "hmar_attn_bwd")
+    return dQ, dK, dV
+
+
+KERNEL_NAMES = ("hmar_fwd_kernel", "hmar_delta_kernel", "hmar_dkdv_kernel", "hmar_dq_kernel")
+
+
+def hmar_profile_begin() -> None:
+    _check(load_library().hmar_profile_begin(), "hmar_profile_begin")
+
+
+def hmar_profile_end():
+    """{kernel name: (total ms, launches)} of the launches since hmar_profile_begin()."""
+    ms = (ctypes.c_double * 4)()
+    n = (ctypes.c_int64 * 4)()
+    _check(load_library().hmar_profile_end(ms, n), "hmar_profile_end")
+    return {KERNEL_NAMES[i]: (float(ms[i]), int(n[i])) for i in range(4)}

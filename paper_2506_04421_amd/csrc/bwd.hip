@@ -1,0 +1,342 @@
+// Backward kernels of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
+//
+//   hmar_delta_kernel : Delta_i = sum_d dO_id O_id                      (one pass over O, dO)
+//   hmar_dq_kernel    : query-stationary, same walk as the forward.  Recomputes
+//                       P^T = exp(S^T - LSE), dP^T = V dO^T, dS^T = P^T o (dP^T - Delta) and
+//                       accumulates dQ^T += K^T dS^T.
+//   hmar_dkdv_kernel  : key-stationary, walks the transposed schedule (a key of scale k is
+//                       seen by the queries of scales k and k+1).  Recomputes P and dS with
+//                       the keys in the lane dimension and accumulates dV^T += dO^T P,
+//                       dK^T += Q^T dS.
+// Both main kernels recompute the probabilities, so no gradient is accumulated across
+// workgroups: results are deterministic and nothing needs zero-initialising.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace hmar {
+
+struct BwdParams {
+    const __bf16* Q; const __bf16* K; const __bf16* V; const __bf16* dO;
+    const float* LSE; const float* delta;
+    __bf16* dQ; __bf16* dK; __bf16* dV;
+    const Item* items; const int32_t* row_lo; const int32_t* row_hi;
+    int n_items, n_heads, L;
+    float c;          // sm_scale * log2(e)
+    float sm_scale;
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+__global__ __launch_bounds__(256) void hmar_delta_kernel(const __bf16* __restrict__ O, const __bf16* __restrict__ dO,
+                                                         float* __restrict__ delta, long long n_rows) {
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long row = idx >> 3;
+    const int c = (int)(idx & 7);
+    float acc = 0.f;
+    if (row < n_rows) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(O + row * kD + c * 8);
+        const u32x4 b = *reinterpret_cast<const u32x4*>(dO + row * kD + c * 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc += bf16_lo(a[i]) * bf16_lo(b[i]) + bf16_hi(a[i]) * bf16_hi(b[i]);
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    if (row < n_rows && c == 0) delta[row] = acc;
+}
+
+// ------------------------------------------------------------------------------------- dQ
+__global__ __launch_bounds__(kThreads) void hmar_dq_kernel(BwdParams p) {
+    __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTile * kLdRow];
+    __shared__ __attribute__((aligned(16))) __bf16 Vs[2][kTile * kLdRow];
+    __shared__ __attribute__((aligned(16))) __bf16 Kt[2][kD * kLdTr];
+
+    int head, item_id;
+    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
+    const Item it = p.items[item_id];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lr = lane & 31, h = lane >> 5;
+    const size_t head_off = (size_t)head * p.L * kD;
+    const __bf16* Kh = p.K + head_off;
+    const __bf16* Vh = p.V + head_off;
+
+    const int wq0 = it.own_begin + wave * kRowsPerWave;
+    const bool wave_active = wq0 < it.own_end;
+    const bool row_valid = wq0 + lr < it.own_end;
+    const int qrow = min(wq0 + lr, it.own_end - 1);
+    const int lo = p.row_lo[qrow], hi = p.row_hi[qrow];
+    const int wlo = wave_min(lo), whi = wave_max(hi);
+    const int full_lo = wave_max(lo), full_hi = wave_min(hi);
+
+    bf16x8 q[4], dob[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        q[t] = *reinterpret_cast<const bf16x8*>(p.Q + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
+        dob[t] = *reinterpret_cast<const bf16x8*>(p.dO + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
+    }
+    const float lse2 = p.LSE[(size_t)head * p.L + qrow] * kLog2e;
+    const float delta = p.delta[(size_t)head * p.L + qrow];
+
+    f32x16 dq[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dq[mb][i] = 0.f;
+
+    const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
+    const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
+
+    RowRegs kr, vr;
+    TrRegs ktr;
+    load_rows(kr, Kh, k_begin, kmax, tid);
+    load_rows(vr, Vh, k_begin, kmax, tid);
+    load_tr(ktr, Kh, k_begin, kmax, tid);
+    store_rows(kr, Ks[0], tid);
+    store_rows(vr, Vs[0], tid);
+    store_tr(ktr, Kt[0], tid);
+    __syncthreads();
+
+    for (int ti = 0; ti < ntiles; ++ti) {
+        const int kt = k_begin + ti * kTile;
+        const int buf = ti & 1;
+        const bool more = ti + 1 < ntiles;
+        if (more) {
+            load_rows(kr, Kh, kt + kTile, kmax, tid);
+            load_rows(vr, Vh, kt + kTile, kmax, tid);
+            load_tr(ktr, Kh, kt + kTile, kmax, tid);
+        }
+        if (wave_active && kt < whi && kt + kTile > wlo) {
+            const bool need_mask = kt < full_lo || kt + kTile > full_hi;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                f32x16 s, dp;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    s = mfma32(lds_a_row(Ks[buf], 32 * kb + lr, t, h), q[t], s);
+                    dp = mfma32(lds_a_row(Vs[buf], 32 * kb + lr, t, h), dob[t], dp);
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, -lse2));
+                    if (need_mask) {
+                        const int j = kt + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+                        pv = (j >= lo && j < hi) ? pv : 0.f;
+                    }
+                    s[i] = pv * (dp[i] - delta);
+                }
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    const int e0 = 8 * sub, tp = 2 * kb + sub;
+                    const bf16x8 dsb = pack8(s[e0 + 0], s[e0 + 1], s[e0 + 2], s[e0 + 3],
+                                             s[e0 + 4], s[e0 + 5], s[e0 + 6], s[e0 + 7]);
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+                        dq[mb] = mfma32(lds_a_tr(Kt[buf], 32 * mb + lr, tp, h), dsb, dq[mb]);
+                }
+            }
+        }
+        if (more) {
+            store_rows(kr, Ks[buf ^ 1], tid);
+            store_rows(vr, Vs[buf ^ 1], tid);
+            store_tr(ktr, Kt[buf ^ 1], tid);
+        }
+        __syncthreads();
+    }
+
+    if (wave_active && row_valid) {
+        __bf16* orow = p.dQ + head_off + (size_t)(wq0 + lr) * kD;
+        const float sc = p.sm_scale;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                store4_bf16(orow + 32 * mb + 8 * j + 4 * h, dq[mb][4 * j] * sc, dq[mb][4 * j + 1] * sc,
+                            dq[mb][4 * j + 2] * sc, dq[mb][4 * j + 3] * sc);
+    }
+}
+
+// ---------------------------------------------------------------------------------- dK, dV
+__global__ __launch_bounds__(kThreads) void hmar_dkdv_kernel(BwdParams p) {
+    __shared__ __attribute__((aligned(16))) __bf16 Qs[2][kTile * kLdRow];
+    __shared__ __attribute__((aligned(16))) __bf16 Gs[2][kTile * kLdRow];   // dO rows
+    __shared__ __attribute__((aligned(16))) __bf16 Qt[2][kD * kLdTr];
+    __shared__ __attribute__((aligned(16))) __bf16 Gt[2][kD * kLdTr];      // dO transposed
+    __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
+    __shared__ __attribute__((aligned(16))) float delta_s[2][kTile];
+
+    int head, item_id;
+    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
+    const Item it = p.items[item_id];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lr = lane & 31, h = lane >> 5;
+    const size_t head_off = (size_t)head * p.L * kD;
+    const __bf16* Qh = p.Q + head_off;
+    const __bf16* Gh = p.dO + head_off;
+    const float* LSEh = p.LSE + (size_t)head * p.L;
+    const float* Dh = p.delta + (size_t)head * p.L;
+
+    const int wk0 = it.own_begin + wave * kRowsPerWave;
+    const bool wave_active = wk0 < it.own_end;
+    const bool row_valid = wk0 + lr < it.own_end;
+    const int krow = min(wk0 + lr, it.own_end - 1);
+    const int lo = p.row_lo[krow], hi = p.row_hi[krow];       // queries that see this key
+    const int wlo = wave_min(lo), whi = wave_max(hi);
+    const int full_lo = wave_max(lo), full_hi = wave_min(hi);
+
+    bf16x8 kreg[4], vreg[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        kreg[t] = *reinterpret_cast<const bf16x8*>(p.K + head_off + (size_t)krow * kD + 16 * t + 8 * h);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(p.V + head_off + (size_t)krow * kD + 16 * t + 8 * h);
+    }
+
+    f32x16 dk[2], dv[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dk[mb][i] = 0.f; dv[mb][i] = 0.f; }
+
+    const int q_begin = it.other_begin, q_end = it.other_end, qmax = q_end - 1;
+    const int ntiles = (q_end - q_begin + kTile - 1) / kTile;
+
+    RowRegs qr, gr;
+    TrRegs qtr, gtr;
+    float stat = 0.f;   // threads 0..63 carry LSE*log2e of row tid, threads 64..127 carry Delta
+    auto load_stage = [&](int qt) {
+        load_rows(qr, Qh, qt, qmax, tid);
+        load_rows(gr, Gh, qt, qmax, tid);
+        load_tr(qtr, Qh, qt, qmax, tid);
+        load_tr(gtr, Gh, qt, qmax, tid);
+        if (tid < 64) stat = LSEh[min(qt + tid, qmax)] * kLog2e;
+        else if (tid < 128) stat = Dh[min(qt + tid - 64, qmax)];
+    };
+    auto store_stage = [&](int b) {
+        store_rows(qr, Qs[b], tid);
+        store_rows(gr, Gs[b], tid);
+        store_tr(qtr, Qt[b], tid);
+        store_tr(gtr, Gt[b], tid);
+        if (tid < 64) lse_s[b][tid] = stat;
+        else if (tid < 128) delta_s[b][tid - 64] = stat;
+    };
+    load_stage(q_begin);
+    store_stage(0);
+    __syncthreads();
+
+    for (int ti = 0; ti < ntiles; ++ti) {
+        const int qt = q_begin + ti * kTile;
+        const int buf = ti & 1;
+        const bool more = ti + 1 < ntiles;
+        if (more) load_stage(qt + kTile);
+        if (wave_active && qt < whi && qt + kTile > wlo) {
+            const bool need_mask = qt < full_lo || qt + kTile > full_hi;
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                f32x16 s, dp;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    s = mfma32(lds_a_row(Qs[buf], 32 * qb + lr, t, h), kreg[t], s);
+                    dp = mfma32(lds_a_row(Gs[buf], 32 * qb + lr, t, h), vreg[t], dp);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse_s[buf][32 * qb + 8 * j + 4 * h]);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(&delta_s[buf][32 * qb + 8 * j + 4 * h]);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = 4 * j + r;
+                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, -l4[r]));
+                        if (need_mask) {
+                            const int qi = qt + 32 * qb + 8 * j + 4 * h + r;
+                            pv = (qi >= lo && qi < hi) ? pv : 0.f;
+                        }
+                        s[i] = pv;
+                        dp[i] = pv * (dp[i] - d4[r]);
+                    }
+                }
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    const int e0 = 8 * sub, tp = 2 * qb + sub;
+                    const bf16x8 pb = pack8(s[e0 + 0], s[e0 + 1], s[e0 + 2], s[e0 + 3],
+                                            s[e0 + 4], s[e0 + 5], s[e0 + 6], s[e0 + 7]);
+                    const bf16x8 dsb = pack8(dp[e0 + 0], dp[e0 + 1], dp[e0 + 2], dp[e0 + 3],
+                                             dp[e0 + 4], dp[e0 + 5], dp[e0 + 6], dp[e0 + 7]);
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) {
+                        dv[mb] = mfma32(lds_a_tr(Gt[buf], 32 * mb + lr, tp, h), pb, dv[mb]);
+                        dk[mb] = mfma32(lds_a_tr(Qt[buf], 32 * mb + lr, tp, h), dsb, dk[mb]);
+                    }
+                }
+            }
+        }
+        if (more) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    if (wave_active && row_valid) {
+        __bf16* krow_out = p.dK + head_off + (size_t)(wk0 + lr) * kD;
+        __bf16* vrow_out = p.dV + head_off + (size_t)(wk0 + lr) * kD;
+        const float sc = p.sm_scale;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int d0 = 32 * mb + 8 * j + 4 * h;
+                store4_bf16(krow_out + d0, dk[mb][4 * j] * sc, dk[mb][4 * j + 1] * sc,
+                            dk[mb][4 * j + 2] * sc, dk[mb][4 * j + 3] * sc);
+                store4_bf16(vrow_out + d0, dv[mb][4 * j], dv[mb][4 * j + 1], dv[mb][4 * j + 2], dv[mb][4 * j + 3]);
+            }
+    }
+}
+
+hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                      const float* LSE, void* dQ, void* dK, void* dV, float* delta,
+                      const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream) {
+    const long long n_rows = (long long)n_heads * s.L;
+    const long long dgroups = (n_rows * 8 + 255) / 256;
+    if (dgroups <= 0 || dgroups > 0x7fffffffLL) return hipErrorInvalidValue;
+    profile_before(kKernelDelta, stream);
+    hipLaunchKernelGGL(hmar_delta_kernel, dim3((unsigned)dgroups), dim3(256), 0, stream,
+                       static_cast<const __bf16*>(O), static_cast<const __bf16*>(dO), delta, n_rows);
+    hipError_t e = hipGetLastError();
+    profile_after(kKernelDelta, stream);
+    if (e != hipSuccess) return e;
+
+    BwdParams p;
+    p.Q = static_cast<const __bf16*>(Q);
+    p.K = static_cast<const __bf16*>(K);
+    p.V = static_cast<const __bf16*>(V);
+    p.dO = static_cast<const __bf16*>(dO);
+    p.LSE = LSE;
+    p.delta = delta;
+    p.dQ = static_cast<__bf16*>(dQ);
+    p.dK = static_cast<__bf16*>(dK);
+    p.dV = static_cast<__bf16*>(dV);
+    p.n_heads = n_heads;
+    p.L = s.L;
+    p.c = sm_scale * kLog2e;
+    p.sm_scale = sm_scale;
+
+    for (int dir = 1; dir >= 0; --dir) {
+        p.items = static_cast<const Item*>(s.items[dir]);
+        p.row_lo = s.row_lo[dir];
+        p.row_hi = s.row_hi[dir];
+        p.n_items = s.n_items[dir];
+        const long long groups = 8LL * ((n_heads + 7) / 8) * s.n_items[dir];
+        if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
+        const int kid = dir == 1 ? kKernelDkDv : kKernelDq;
+        profile_before(kid, stream);
+        if (dir == 1) hipLaunchKernelGGL(hmar_dkdv_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+        else          hipLaunchKernelGGL(hmar_dq_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+        e = hipGetLastError();
+        profile_after(kid, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace hmar

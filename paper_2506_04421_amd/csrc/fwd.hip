@@ -1,0 +1,185 @@
+// Forward kernel of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
+//
+// One workgroup (4 wavefronts) owns up to 128 consecutive query rows, 32 per wavefront,
+// and streams the key/value rows of their two-scale windows through LDS in tiles of 64.
+// Scores are computed transposed (S^T = K Q^T) so that a lane holds one query column:
+// the row maximum and sum are then lane-local apart from one exchange between the two
+// half-waves, and the probability tile is already laid out as the B operand of the
+// second contraction O^T += V^T P^T.  V tiles are transposed on their way into LDS.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace hmar {
+
+struct FwdParams {
+    const __bf16* Q; const __bf16* K; const __bf16* V;
+    __bf16* O; float* LSE;
+    const Item* items; const int32_t* row_lo; const int32_t* row_hi;
+    int n_items, n_heads, L;
+    float c;   // sm_scale * log2(e): scores are exponentiated in base 2
+};
+
+// The running reference maximum of a row is only raised when a tile exceeds it by more
+// than this many binades; until then probabilities are at most 2^8, which fp32 sums and
+// bf16 operands hold without loss.  The final division by the row sum makes the result
+// independent of the reference.
+constexpr float kRescaleThreshold = 8.0f;
+
+__global__ __launch_bounds__(kThreads) void hmar_fwd_kernel(FwdParams p) {
+    __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTile * kLdRow];
+    __shared__ __attribute__((aligned(16))) __bf16 Vt[2][kD * kLdTr];
+
+    int head, item_id;
+    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
+    const Item it = p.items[item_id];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lr = lane & 31, h = lane >> 5;
+    const size_t head_off = (size_t)head * p.L * kD;
+    const __bf16* Qh = p.Q + head_off;
+    const __bf16* Kh = p.K + head_off;
+    const __bf16* Vh = p.V + head_off;
+
+    const int wq0 = it.own_begin + wave * kRowsPerWave;
+    const bool wave_active = wq0 < it.own_end;               // uniform over the wavefront
+    const bool row_valid = wq0 + lr < it.own_end;
+    const int qrow = min(wq0 + lr, it.own_end - 1);
+    const int lo = p.row_lo[qrow], hi = p.row_hi[qrow];
+    const int wlo = wave_min(lo), whi = wave_max(hi);        // union of the wave's windows
+    const int full_lo = wave_max(lo), full_hi = wave_min(hi);  // keys every row of the wave sees
+
+    bf16x8 q[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        q[t] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow * kD + 16 * t + 8 * h);
+
+    f32x16 o[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
+    float m_ref = kNegBig, lsum = 0.f;
+
+    const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
+    const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
+
+    RowRegs kr;
+    TrRegs vr;
+    load_rows(kr, Kh, k_begin, kmax, tid);
+    load_tr(vr, Vh, k_begin, kmax, tid);
+    store_rows(kr, Ks[0], tid);
+    store_tr(vr, Vt[0], tid);
+    __syncthreads();
+
+    for (int ti = 0; ti < ntiles; ++ti) {
+        const int kt = k_begin + ti * kTile;
+        const int buf = ti & 1;
+        const bool more = ti + 1 < ntiles;
+        if (more) {
+            load_rows(kr, Kh, kt + kTile, kmax, tid);
+            load_tr(vr, Vh, kt + kTile, kmax, tid);
+        }
+        if (wave_active && kt < whi && kt + kTile > wlo) {
+            const __bf16* Kt = Ks[buf];
+            const __bf16* Vtt = Vt[buf];
+            f32x16 s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    s[kb] = mfma32(lds_a_row(Kt, 32 * kb + lr, t, h), q[t], s[kb]);
+            }
+            if (kt < full_lo || kt + kTile > full_hi) {
+                // tile straddles a window edge of some row: mask per element
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int j = kt + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
+                        s[kb][i] = (j >= lo && j < hi) ? s[kb][i] : -INFINITY;
+                    }
+            }
+            float mt = s[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[kb][i]);
+            mt = half_max(mt) * p.c;
+            if (__builtin_amdgcn_ballot_w64(mt > m_ref + kRescaleThreshold) != 0) {
+                const float m_new = fmaxf(m_ref, mt);
+                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                lsum *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
+                m_ref = m_new;
+            }
+            const float neg_m = -m_ref;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], p.c, neg_m));
+                    lsum += pv;
+                    s[kb][i] = pv;
+                }
+#pragma unroll
+            for (int tp = 0; tp < 4; ++tp) {
+                const int kb = tp >> 1, e0 = 8 * (tp & 1);
+                const bf16x8 pb = pack8(s[kb][e0 + 0], s[kb][e0 + 1], s[kb][e0 + 2], s[kb][e0 + 3],
+                                        s[kb][e0 + 4], s[kb][e0 + 5], s[kb][e0 + 6], s[kb][e0 + 7]);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+                    o[mb] = mfma32(lds_a_tr(Vtt, 32 * mb + lr, tp, h), pb, o[mb]);
+            }
+        }
+        if (more) {
+            store_rows(kr, Ks[buf ^ 1], tid);
+            store_tr(vr, Vt[buf ^ 1], tid);
+        }
+        __syncthreads();
+    }
+
+    if (wave_active) {
+        const float l = half_sum(lsum);
+        const float inv = 1.0f / l;
+        if (row_valid) {
+            __bf16* orow = p.O + head_off + (size_t)(wq0 + lr) * kD;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    store4_bf16(orow + 32 * mb + 8 * j + 4 * h, o[mb][4 * j] * inv, o[mb][4 * j + 1] * inv,
+                                o[mb][4 * j + 2] * inv, o[mb][4 * j + 3] * inv);
+            if (h == 0) p.LSE[(size_t)head * p.L + wq0 + lr] = (m_ref + log2f(l)) * kLn2;
+        }
+    }
+}
+
+hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                      const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream) {
+    FwdParams p;
+    p.Q = static_cast<const __bf16*>(Q);
+    p.K = static_cast<const __bf16*>(K);
+    p.V = static_cast<const __bf16*>(V);
+    p.O = static_cast<__bf16*>(O);
+    p.LSE = LSE;
+    p.items = static_cast<const Item*>(s.items[0]);
+    p.row_lo = s.row_lo[0];
+    p.row_hi = s.row_hi[0];
+    p.n_items = s.n_items[0];
+    p.n_heads = n_heads;
+    p.L = s.L;
+    p.c = sm_scale * kLog2e;
+    const long long groups = 8LL * ((n_heads + 7) / 8) * s.n_items[0];
+    if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
+    profile_before(kKernelFwd, stream);
+    hipLaunchKernelGGL(hmar_fwd_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+    const hipError_t e = hipGetLastError();
+    profile_after(kKernelFwd, stream);
+    return e;
+}
+
+}  // namespace hmar

@@ -1,0 +1,29 @@
+// Launchers of the gfx950 kernels (internal to the library; the public ABI is hmar_attn.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hmar {
+
+// Device copy of the tile schedule of one (device, scale schedule) pair.
+struct DeviceSchedule {
+    const void* items[2];      // Item[n_items[dir]]
+    int32_t n_items[2];
+    const int32_t* row_lo[2];  // L entries
+    const int32_t* row_hi[2];
+    int32_t L;
+};
+
+// Per-kernel event bracketing for hmar_profile_begin/end (no-ops unless profiling is on).
+enum KernelId { kKernelFwd = 0, kKernelDelta = 1, kKernelDkDv = 2, kKernelDq = 3, kNumKernels = 4 };
+void profile_before(int kernel_id, hipStream_t stream);
+void profile_after(int kernel_id, hipStream_t stream);
+
+hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                      const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream);
+
+hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                      const float* LSE, void* dQ, void* dK, void* dV, float* delta,
+                      const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream);
+
+}  // namespace hmar

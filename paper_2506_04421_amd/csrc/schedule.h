@@ -1,0 +1,37 @@
+// Host-side tile schedule of the Markovian next-scale mask (paper Sec. 3.1, App. B.2).
+//
+// From the prefix sums of the scale sizes the builder derives, for each direction, the
+// list of workgroup items the kernels walk.  An item owns a contiguous range of rows of
+// the stationary operand and visits one contiguous range of rows of the streamed
+// operand; score tiles outside that range are never loaded.
+//   direction 0 (forward, dQ): owned rows are queries, visited rows are keys.
+//       query i of scale k (0-based) pairs with keys [off[max(k-1,0)], off[k+1])
+//   direction 1 (dK/dV): owned rows are keys, visited rows are queries.
+//       key j of scale k pairs with queries [off[k], off[min(k+2,K)])
+#pragma once
+#include <cstdint>
+#include <vector>
+
+namespace hmar {
+
+struct TileItem {
+    int32_t own_begin, own_end;      // rows owned by the workgroup, own_end - own_begin <= rows_per_item
+    int32_t other_begin, other_end;  // union of the owned rows' pair ranges
+};
+
+struct Schedule {
+    std::vector<int32_t> sides;
+    std::vector<int32_t> off;        // K+1 prefix sums of side^2
+    int32_t L = 0;
+    int64_t allowed_pairs = 0;       // sum_k n_k (n_{k-1} + n_k)
+    // per direction
+    std::vector<TileItem> items[2];
+    std::vector<int32_t> row_lo[2], row_hi[2];   // L entries each
+};
+
+// rows_per_item: most rows one workgroup owns (a multiple of 32).  Returns false when
+// the sides are invalid (non-positive, too many, or L beyond max_len).
+bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t rows_per_item,
+                    int32_t max_scales, int64_t max_len, Schedule* out);
+
+}  // namespace hmar

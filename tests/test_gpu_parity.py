@@ -1,0 +1,213 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle.
+
+Bars (from the target statement): max-abs 2e-2 on the bf16 outputs and gradients,
+|LSE - ref| <= 1e-4 * max(1, |ref|) on the fp32 log-sum-exp.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2506_04421_amd as hm
+from oracle import hmar_attn_oracle as orc
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+TOL_ABS = 2e-2
+TOL_LSE_REL = 1e-4
+
+
+def _dev():
+    return torch.device("cuda:0")
+
+
+def _oracle_heads(Q, K, V, dO, sides, sm_scale, heads):
+    """Oracle forward+backward on selected (b, h) slices; returns dict of fp64 arrays [n, L, *]."""
+    out = {k: [] for k in ("O", "LSE", "dQ", "dK", "dV")}
+    for (b, h) in heads:
+        q, k, v = (si.to_f64(t[b, h])[None, None] for t in (Q, K, V))
+        O, LSE = orc.attn_fwd(q, k, v, sides, sm_scale)
+        out["O"].append(O[0, 0])
+        out["LSE"].append(LSE[0, 0])
+        if dO is not None:
+            g = si.to_f64(dO[b, h])[None, None]
+            dQ, dK, dV = orc.attn_bwd(q, k, v, g, sides, sm_scale)
+            out["dQ"].append(dQ[0, 0]); out["dK"].append(dK[0, 0]); out["dV"].append(dV[0, 0])
+    return {k: np.stack(v) for k, v in out.items() if v}
+
+
+def _gpu_run(Q, K, V, dO, sides, sm_scale, backward=True):
+    d = _dev()
+    q, k, v = (t.to(d) for t in (Q, K, V))
+    O, LSE = hm.hmar_attn_fwd(q, k, v, sides, sm_scale)
+    res = {"O": O, "LSE": LSE}
+    if backward:
+        g = dO.to(d)
+        dQ, dK, dV = hm.hmar_attn_bwd(q, k, v, O, g, LSE, sides, sm_scale)
+        res.update(dQ=dQ, dK=dK, dV=dV)
+    torch.cuda.synchronize()
+    return res
+
+
+def _compare(res, ref, heads, label, scale_with_magnitude=False):
+    for name in ("O", "dQ", "dK", "dV"):
+        if name not in res or name not in ref:
+            continue
+        got = np.stack([si.to_f64(res[name][b, h]) for (b, h) in heads])
+        assert np.isfinite(got).all(), (label, name, "non-finite")
+        err = np.abs(got - ref[name]).max()
+        tol = TOL_ABS
+        if scale_with_magnitude:
+            # 2e-2 is stated for N(0,1) inputs, whose results stay below ~4 in magnitude
+            # (one bf16 rounding of the result is then <= 2^-9 * 4 = 7.8e-3).  Inputs scaled
+            # up on purpose give larger gradients; the bar keeps the same ratio to them.
+            tol = TOL_ABS * max(1.0, float(np.abs(ref[name]).max()) / 4.0)
+        assert err <= tol, (label, name, float(err), tol)
+    got = np.stack([si.to_f64(res["LSE"][b, h]) for (b, h) in heads])
+    bound = TOL_LSE_REL * np.maximum(1.0, np.abs(ref["LSE"]))
+    assert (np.abs(got - ref["LSE"]) <= bound).all(), (label, "LSE", float(np.abs(got - ref["LSE"]).max()))
+
+
+def _all_heads(B, H):
+    return [(b, h) for b in range(B) for h in range(H)]
+
+
+def _sample_heads(B, H, n, seed):
+    rng = np.random.default_rng(seed)
+    idx = rng.choice(B * H, size=min(n, B * H), replace=False)
+    heads = sorted({(int(i) // H, int(i) % H) for i in idx} | {(0, 0), (B - 1, H - 1)})
+    return heads
+
+
+def test_tiny_config_forward_and_backward():
+    w = si.WORKLOADS["tiny"]
+    Q, K, V, dO = si.make_inputs(w)
+    sm = 1.0 / math.sqrt(w.D)
+    res = _gpu_run(Q, K, V, dO, w.sides, sm)
+    heads = _all_heads(w.B, w.H)
+    _compare(res, _oracle_heads(Q, K, V, dO, w.sides, sm, heads), heads, "tiny")
+
+
+ODD_SCHEDULES = [(1,), (2,), (7,), (8,), (12,), (1, 1, 1), (2, 5), (3, 1, 4, 1, 5), (12, 12), (9, 8),
+                 (20, 3, 20), (5, 11, 2, 11), tuple(range(1, 17)), (6, 7, 8, 9, 10)]
+
+
+@pytest.mark.parametrize("sides", ODD_SCHEDULES, ids=lambda s: "x".join(map(str, s)))
+def test_ragged_and_degenerate_schedules(sides):
+    # single-token, single-scale, equal scales, shrinking scales, many small scales:
+    # every tile edge and merge rule of the schedule builder is crossed
+    L = sum(s * s for s in sides)
+    B, H, D = 2, 3, 64
+    Q, K, V, dO = si.draw((B, H, L, D), seed=100 + L, n_tensors=4)
+    res = _gpu_run(Q, K, V, dO, sides, 0.0)          # sm_scale <= 0 selects 1/sqrt(D)
+    heads = _all_heads(B, H)
+    _compare(res, _oracle_heads(Q, K, V, dO, sides, 1.0 / math.sqrt(D), heads), heads, str(sides))
+
+
+@pytest.mark.parametrize("name,n_heads", [("256px_b16_h16", 10), ("256px_b32_h24", 8), ("256px_b32_h30", 4),
+                                          ("512px_b8_h24", 3)])
+def test_full_size_workloads_on_sampled_heads(name, n_heads):
+    # full problem size in the launch configuration the benchmark times; the oracle is
+    # evaluated on a seeded sample of (b, h) slices, each compared in full
+    w = si.WORKLOADS[name]
+    Q, K, V, dO = si.make_inputs(w)
+    sm = 1.0 / math.sqrt(w.D)
+    res = _gpu_run(Q, K, V, dO, w.sides, sm)
+    heads = _sample_heads(w.B, w.H, n_heads, seed=w.seed)
+    _compare(res, _oracle_heads(Q, K, V, dO, w.sides, sm, heads), heads, name)
+    # properties that hold at any size, over every head
+    for t in res.values():
+        assert torch.isfinite(t.float()).all()
+    # scale 1 has one token that sees only itself: O[...,0,:] == V[...,0,:] exactly
+    assert torch.equal(res["O"][:, :, 0, :].cpu(), V[:, :, 0, :])
+
+
+def test_large_scores_exercise_the_running_maximum():
+    # scores of magnitude ~30-40: the running reference maximum must be raised mid-window
+    sides = si.SIDES_256
+    L, B, H, D = 680, 1, 4, 64
+    Q, K, V, dO = si.draw((B, H, L, D), seed=7, n_tensors=4)
+    Q = (Q.float() * 6.0).to(torch.bfloat16)
+    # make later keys systematically larger so the maximum keeps growing along a window
+    ramp = torch.linspace(0.5, 1.5, L).view(1, 1, L, 1)
+    K = (K.float() * ramp).to(torch.bfloat16)
+    res = _gpu_run(Q, K, V, dO, sides, 0.125)
+    heads = _all_heads(B, H)
+    _compare(res, _oracle_heads(Q, K, V, dO, sides, 0.125, heads), heads, "large-scores",
+             scale_with_magnitude=True)
+
+
+def test_custom_softmax_scale():
+    sides = (3, 6, 9)
+    L, B, H, D = 126, 1, 2, 64
+    Q, K, V, dO = si.draw((B, H, L, D), seed=8, n_tensors=4)
+    res = _gpu_run(Q, K, V, dO, sides, 0.3)
+    heads = _all_heads(B, H)
+    _compare(res, _oracle_heads(Q, K, V, dO, sides, 0.3, heads), heads, "scale0.3")
+
+
+def test_results_are_deterministic_and_inputs_untouched():
+    w = si.WORKLOADS["256px_b16_h16"]
+    Q, K, V, dO = si.draw((2, 4, w.L, w.D), seed=9, n_tensors=4)
+    d = _dev()
+    q, k, v, g = (t.to(d) for t in (Q, K, V, dO))
+    a = hm.hmar_attn_fwd(q, k, v, w.sides)
+    ga = hm.hmar_attn_bwd(q, k, v, a[0], g, a[1], w.sides)
+    b = hm.hmar_attn_fwd(q, k, v, w.sides)
+    gb = hm.hmar_attn_bwd(q, k, v, b[0], g, b[1], w.sides)
+    torch.cuda.synchronize()
+    for x, y in zip(a + ga, b + gb):
+        assert torch.equal(x, y)
+    for x, y in zip((q, k, v, g), (Q, K, V, dO)):
+        assert torch.equal(x.cpu(), y)
+
+
+def test_guard_bands_stay_intact_and_do_not_leak():
+    # tensors live inside larger buffers whose surroundings are NaN: nothing outside the
+    # tensors may be read into a result or written
+    sides = (1, 2, 3, 4, 5, 6, 8)       # L = 155, ragged last tiles
+    L, B, H, D = 155, 2, 2, 64
+    n = B * H * L * D
+    pad = 4096
+    d = _dev()
+    host = si.draw((B, H, L, D), seed=10, n_tensors=4)
+
+    def guarded(t=None, dtype=torch.bfloat16, count=n):
+        buf = torch.full((count + 2 * pad,), float("nan"), dtype=dtype, device=d)
+        view = buf[pad:pad + count]
+        if t is not None:
+            view.copy_(t.reshape(-1).to(d))
+        return buf, view
+
+    bq, q = guarded(host[0]); bk, k = guarded(host[1]); bv, v = guarded(host[2]); bg, g = guarded(host[3])
+    bo, o = guarded(); bdq, dq = guarded(); bdk, dk = guarded(); bdv, dv = guarded()
+    bl, lse = guarded(dtype=torch.float32, count=B * H * L)
+    shp = (B, H, L, D)
+    O, LSE = hm.hmar_attn_fwd(q.view(shp), k.view(shp), v.view(shp), sides, 0.0, O=o.view(shp), LSE=lse.view(B, H, L))
+    dQ, dK, dV = hm.hmar_attn_bwd(q.view(shp), k.view(shp), v.view(shp), O, g.view(shp), LSE, sides, 0.0,
+                                  dQ=dq.view(shp), dK=dk.view(shp), dV=dv.view(shp))
+    torch.cuda.synchronize()
+    for buf, cnt in ((bo, n), (bdq, n), (bdk, n), (bdv, n), (bl, B * H * L)):
+        assert torch.isnan(buf[:pad]).all() and torch.isnan(buf[pad + cnt:]).all()
+        assert torch.isfinite(buf[pad:pad + cnt].float()).all()
+    heads = _all_heads(B, H)
+    res = dict(O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV)
+    _compare(res, _oracle_heads(*host, sides, 0.125, heads), heads, "guarded")
+
+
+def test_runs_on_a_side_stream():
+    w = si.WORKLOADS["tiny"]
+    Q, K, V, dO = si.make_inputs(w)
+    d = _dev()
+    q, k, v, g = (t.to(d) for t in (Q, K, V, dO))
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream(device=d)
+    with torch.cuda.stream(s):
+        O, LSE = hm.hmar_attn_fwd(q, k, v, w.sides)
+        dQ, dK, dV = hm.hmar_attn_bwd(q, k, v, O, g, LSE, w.sides)
+    s.synchronize()
+    heads = _all_heads(w.B, w.H)
+    _compare(dict(O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV),
+             _oracle_heads(Q, K, V, dO, w.sides, 0.125, heads), heads, "side-stream")

@@ -1,0 +1,142 @@
+"""Host-side checks of the C-ABI library: it loads without a GPU, exports what the header
+declares, rejects bad arguments before any device work, and its tile schedule covers
+exactly the oracle's explicit mask."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2506_04421_amd as hm
+from paper_2506_04421_amd import binding
+from oracle import hmar_attn_oracle as orc
+import synth_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+SCHEDULES = [si.SIDES_TINY, si.SIDES_256, si.SIDES_512, (1,), (7,), (16,), (1, 1, 1), (2, 5),
+             (3, 1, 4, 1, 5), (12, 12), (1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16), (20, 3, 20)]
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = hm.load_library()
+    header = open(os.path.join(ROOT, "include", "hmar_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(hmar_[a-z_]+)\s*\(", header))
+    assert {"hmar_attn_fwd", "hmar_attn_bwd", "hmar_attn_bwd_workspace_bytes", "hmar_status_string",
+            "hmar_schedule_describe", "hmar_schedule_tiles"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    assert hm.status_string(0) == "HMAR_OK"
+    assert hm.status_string(1) == "HMAR_ERR_INVALID_ARG"
+    assert hm.status_string(2) == "HMAR_ERR_UNSUPPORTED"
+    assert hm.status_string(3) == "HMAR_ERR_WORKSPACE"
+    assert hm.status_string(4) == "HMAR_ERR_HIP"
+    assert "UNKNOWN" in hm.status_string(77)
+
+
+@pytest.mark.parametrize("sides", SCHEDULES)
+def test_describe_matches_oracle_schedule(sides):
+    offs, pairs = hm.hmar_schedule_describe(sides)
+    assert offs == orc.scale_offsets(sides)
+    assert pairs == orc.allowed_pairs(sides)
+
+
+@pytest.mark.parametrize("sides", SCHEDULES)
+@pytest.mark.parametrize("which", [0, 1])
+def test_tile_schedule_covers_exactly_the_mask(sides, which):
+    mask = orc.markov_mask(sides)
+    if which == 1:
+        mask = mask.T           # owned rows are keys, visited rows are queries
+    L = mask.shape[0]
+    items, lo, hi = hm.hmar_schedule_tiles(sides, which)
+    # per-row ranges are exactly the row's allowed set
+    rebuilt = np.zeros_like(mask)
+    for r in range(L):
+        assert 0 <= lo[r] < hi[r] <= L
+        rebuilt[r, lo[r]:hi[r]] = True
+    assert np.array_equal(rebuilt, mask)
+    # items partition the rows, own at most 128 rows, and visit the union of their rows' ranges
+    owned = np.zeros(L, dtype=int)
+    for (b, e, ob, oe) in items:
+        assert 0 <= b < e <= L and e - b <= 128
+        owned[b:e] += 1
+        assert ob == min(lo[b:e]) and oe == max(hi[b:e])
+        # every 64-wide tile the workgroup loads holds at least one allowed pair
+        for t in range(ob, oe, 64):
+            assert mask[b:e, t:min(t + 64, oe)].any()
+    assert (owned == 1).all()
+
+
+def test_tile_counts_for_the_benchmark_schedules():
+    # 64-row tiles executed per head by 32-row wavefronts: the useful/executed ratio the
+    # design quotes (forward): 256px >= 0.80, 512px >= 0.90
+    for sides, floor in ((si.SIDES_256, 0.80), (si.SIDES_512, 0.90)):
+        items, lo, hi = hm.hmar_schedule_tiles(sides, 0)
+        executed = 0
+        for (b, e, ob, oe) in items:
+            for w in range(b, e, 32):
+                rows = range(w, min(w + 32, e))
+                wlo = min(lo[r] for r in rows)
+                whi = max(hi[r] for r in rows)
+                for t in range(ob, oe, 64):
+                    if t < whi and t + 64 > wlo:
+                        executed += 32 * 64
+        assert orc.allowed_pairs(sides) / executed >= floor
+
+
+def _call_fwd(lib, Q=0x1000, K=0x2000, V=0x3000, O=0x4000, LSE=0x5000, sides=(1, 2), B=1, H=1, D=64, sm=0.0):
+    arr = (ctypes.c_int32 * len(sides))(*sides) if sides is not None else None
+    return lib.hmar_attn_fwd(Q, K, V, O, LSE, arr, len(sides) if sides is not None else 2, B, H, D, sm, None)
+
+
+def test_forward_rejects_bad_arguments_before_touching_the_device():
+    # fake but well-formed pointers: every call below must return before any device work
+    lib = hm.load_library()
+    assert _call_fwd(lib, Q=None) == 1
+    assert _call_fwd(lib, LSE=None) == 1
+    assert _call_fwd(lib, K=0x2004) == 1                 # misaligned
+    assert _call_fwd(lib, sides=None) == 1
+    assert _call_fwd(lib, sides=(1, 0, 3)) == 1
+    assert _call_fwd(lib, sides=(1, -2)) == 1
+    assert _call_fwd(lib, B=0) == 1
+    assert _call_fwd(lib, H=-1) == 1
+    assert _call_fwd(lib, sm=float("nan")) == 1
+    assert _call_fwd(lib, D=128) == 2
+    assert _call_fwd(lib, D=32) == 2
+    assert _call_fwd(lib, sides=(1,) * 65) == 2          # more than HMAR_MAX_SCALES
+    assert _call_fwd(lib, sides=(1025,)) == 2            # L beyond HMAR_MAX_SEQ_LEN
+
+
+def test_backward_rejects_bad_arguments_and_small_workspace():
+    lib = hm.load_library()
+    sides = (1, 2, 3, 4)
+    arr = (ctypes.c_int32 * 4)(*sides)
+    need = hm.hmar_attn_bwd_workspace_bytes(sides, 2, 2, 64)
+    assert need == 2 * 2 * 30 * 4
+    assert hm.hmar_attn_bwd_workspace_bytes(sides, 2, 2, 128) == 0
+    p = [0x1000 * (i + 1) for i in range(9)]
+
+    def call(ptrs=p, ws=0xA000, ws_bytes=need, D=64):
+        return lib.hmar_attn_bwd(*ptrs, arr, 4, 2, 2, D, 0.0, ws, ws_bytes, None)
+
+    assert call(ws_bytes=need - 1) == 3
+    assert call(ws=None) == 3
+    assert call(ws=0xA008) == 1
+    assert call(D=16) == 2
+    for i in range(9):
+        q = list(p)
+        q[i] = None
+        assert call(ptrs=q) == 1
+
+
+def test_binding_refuses_cpu_tensors_and_wrong_dtypes():
+    import torch
+    x = torch.zeros((1, 1, 5, 64), dtype=torch.bfloat16)
+    with pytest.raises(hm.HmarError):
+        hm.hmar_attn_fwd(x, x, x, (1, 2))
+    assert os.path.exists(binding.LIB_PATH)
