@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void hmar_delta_kernel(const __bf16* __restric
 }
 
 // ------------------------------------------------------------------------------------- dQ
-__global__ __launch_bounds__(kThreads) void hmar_dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
     __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTile * kLdRow];
     __shared__ __attribute__((aligned(16))) __bf16 Vs[2][kTile * kLdRow];
     __shared__ __attribute__((aligned(16))) __bf16 Kt[2][kD * kLdTr];
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void hmar_dq_kernel(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------- dK, dV
-__global__ __launch_bounds__(kThreads) void hmar_dkdv_kernel(BwdParams p) {
+__global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
     __shared__ __attribute__((aligned(16))) __bf16 Qs[2][kTile * kLdRow];
     __shared__ __attribute__((aligned(16))) __bf16 Gs[2][kTile * kLdRow];   // dO rows
     __shared__ __attribute__((aligned(16))) __bf16 Qt[2][kD * kLdTr];

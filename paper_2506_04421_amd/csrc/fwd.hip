@@ -25,7 +25,7 @@ struct FwdParams {
 // independent of the reference.
 constexpr float kRescaleThreshold = 8.0f;
 
-__global__ __launch_bounds__(kThreads) void hmar_fwd_kernel(FwdParams p) {
+__global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
     __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTile * kLdRow];
     __shared__ __attribute__((aligned(16))) __bf16 Vt[2][kD * kLdTr];
 

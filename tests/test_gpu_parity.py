@@ -51,23 +51,49 @@ def _gpu_run(Q, K, V, dO, sides, sm_scale, backward=True):
     return res
 
 
-def _compare(res, ref, heads, label, scale_with_magnitude=False):
+def _compare(res, ref, heads, label, grad_bounds=None):
     for name in ("O", "dQ", "dK", "dV"):
         if name not in res or name not in ref:
             continue
         got = np.stack([si.to_f64(res[name][b, h]) for (b, h) in heads])
         assert np.isfinite(got).all(), (label, name, "non-finite")
-        err = np.abs(got - ref[name]).max()
-        tol = TOL_ABS
-        if scale_with_magnitude:
-            # 2e-2 is stated for N(0,1) inputs, whose results stay below ~4 in magnitude
-            # (one bf16 rounding of the result is then <= 2^-9 * 4 = 7.8e-3).  Inputs scaled
-            # up on purpose give larger gradients; the bar keeps the same ratio to them.
-            tol = TOL_ABS * max(1.0, float(np.abs(ref[name]).max()) / 4.0)
-        assert err <= tol, (label, name, float(err), tol)
+        err = np.abs(got - ref[name])
+        if grad_bounds is not None and name in grad_bounds:
+            assert (err <= grad_bounds[name]).all(), (label, name, float((err - grad_bounds[name]).max()))
+        else:
+            assert err.max() <= TOL_ABS, (label, name, float(err.max()))
     got = np.stack([si.to_f64(res["LSE"][b, h]) for (b, h) in heads])
     bound = TOL_LSE_REL * np.maximum(1.0, np.abs(ref["LSE"]))
     assert (np.abs(got - ref["LSE"]) <= bound).all(), (label, "LSE", float(np.abs(got - ref["LSE"]).max()))
+
+
+def _operand_rounding_bounds(Q, K, V, dO, sides, sm_scale, heads, ref):
+    """Element-wise error bounds for gradients of inputs scaled up on purpose.
+
+    The path rounds P and dS to bf16 (relative error <= 2^-9) before the second
+    contraction, so the error of sm_scale * sum_j dS_ij K_jd is at most
+    2^-9 * sm_scale * sum_j |dS_ij| |K_jd|, and likewise for dK and dV.  With N(0,1)
+    inputs that is far inside 2e-2; with peaked softmaxes |dS| reaches O(10) and the
+    flat bar no longer describes the arithmetic.  Delta_i = sum_d dO_id O_id is formed from
+    the bf16-rounded forward output, so it is off by up to 2^-9 sum_d |dO_id O_id|, which
+    moves dS_ij by P_ij times that.  Slack: 1.5x, plus one rounding of the result and a
+    2e-3 floor.
+    """
+    eps = 2.0 ** -9
+    mask = orc.markov_mask(sides)
+    out = {"dQ": [], "dK": [], "dV": []}
+    for n, (b, h) in enumerate(heads):
+        q, k, v, g = (si.to_f64(t[b, h]) for t in (Q, K, V, dO))
+        _, _, P = orc.attn_fwd_masked(q, k, v, mask, sm_scale)
+        dP = g @ v.T
+        dS = np.abs(P * (dP - (P * dP).sum(-1, keepdims=True)))
+        d_delta = eps * (np.abs(g) * np.abs(ref["O"][n])).sum(-1, keepdims=True)      # [L, 1]
+        out["dQ"].append(1.5 * sm_scale * (eps * dS @ np.abs(k) + d_delta * np.abs(P @ k))
+                         + 2 * eps * np.abs(ref["dQ"][n]) + 2e-3)
+        out["dK"].append(1.5 * sm_scale * (eps * dS.T @ np.abs(q) + P.T @ (d_delta * np.abs(q)))
+                         + 2 * eps * np.abs(ref["dK"][n]) + 2e-3)
+        out["dV"].append(1.5 * eps * P.T @ np.abs(g) + 2 * eps * np.abs(ref["dV"][n]) + 2e-3)
+    return {k: np.stack(x) for k, x in out.items()}
 
 
 def _all_heads(B, H):
@@ -135,8 +161,11 @@ def test_large_scores_exercise_the_running_maximum():
     K = (K.float() * ramp).to(torch.bfloat16)
     res = _gpu_run(Q, K, V, dO, sides, 0.125)
     heads = _all_heads(B, H)
-    _compare(res, _oracle_heads(Q, K, V, dO, sides, 0.125, heads), heads, "large-scores",
-             scale_with_magnitude=True)
+    ref = _oracle_heads(Q, K, V, dO, sides, 0.125, heads)
+    # forward (where the running maximum lives) at the flat bar; gradients at the bound the
+    # bf16 operand rounding implies for these peaked softmaxes
+    _compare(res, ref, heads, "large-scores",
+             grad_bounds=_operand_rounding_bounds(Q, K, V, dO, sides, 0.125, heads, ref))
 
 
 def test_custom_softmax_scale():
