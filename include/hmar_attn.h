@@ -60,7 +60,7 @@ hmar_status hmar_attn_fwd(const void* Q, const void* K, const void* V, void* O, 
                           int32_t B, int32_t H, int32_t D, float sm_scale, void* stream);
 
 /* Bytes of device workspace hmar_attn_bwd needs for this problem (0 on invalid arguments).
- * The workspace holds Delta_i = sum_d dO_id O_id as fp32 [B,H,L]. */
+ * The workspace holds two fp32 [B,H,L] arrays: Delta_i = sum_d dO_id O_id and -LSE_i*log2(e). */
 size_t hmar_attn_bwd_workspace_bytes(const int32_t* side_lens, int32_t num_scales,
                                      int32_t B, int32_t H, int32_t D);
 

@@ -195,7 +195,7 @@ size_t hmar_attn_bwd_workspace_bytes(const int32_t* side_lens, int32_t num_scale
                                      int32_t B, int32_t H, int32_t D) {
     hmar::Schedule host;
     if (check_problem(side_lens, num_scales, B, H, D, &host) != HMAR_OK) return 0;
-    return (size_t)B * H * host.L * sizeof(float);
+    return 2 * (size_t)B * H * host.L * sizeof(float);
 }
 
 hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
@@ -211,7 +211,7 @@ hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const voi
     hmar::Schedule host;
     hmar_status st = check_problem(side_lens, num_scales, B, H, D, &host);
     if (st != HMAR_OK) return st;
-    const size_t need = (size_t)B * H * host.L * sizeof(float);
+    const size_t need = 2 * (size_t)B * H * host.L * sizeof(float);
     if (!workspace || workspace_bytes < need) return HMAR_ERR_WORKSPACE;
     if (!aligned16(workspace)) return HMAR_ERR_INVALID_ARG;
     const hmar::DeviceSchedule* ds = nullptr;

@@ -1,6 +1,6 @@
 // Backward kernels of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
 //
-//   hmar_delta_kernel : Delta_i = sum_d dO_id O_id                      (one pass over O, dO)
+//   hmar_delta_kernel : Delta_i = sum_d dO_id O_id and -LSE_i * log2(e)   (one pass over O, dO)
 //   hmar_dq_kernel    : query-stationary, same walk as the forward.  Recomputes
 //                       P^T = exp(S^T - LSE), dP^T = V dO^T, dS^T = P^T o (dP^T - Delta) and
 //                       accumulates dQ^T += K^T dS^T.
@@ -9,7 +9,9 @@
 //                       the keys in the lane dimension and accumulates dV^T += dO^T P,
 //                       dK^T += Q^T dS.
 // Both main kernels recompute the probabilities, so no gradient is accumulated across
-// workgroups: results are deterministic and nothing needs zero-initialising.
+// workgroups: results are deterministic and nothing needs zero-initialising.  Streamed
+// tiles are row-major in LDS and serve both as row-wise operands (S, dP) and, through the
+// LDS transpose load, as transposed operands (dQ, dK, dV).
 #include "device_common.h"
 #include "kernels.h"
 
@@ -17,7 +19,8 @@ namespace hmar {
 
 struct BwdParams {
     const __bf16* Q; const __bf16* K; const __bf16* V; const __bf16* dO;
-    const float* LSE; const float* delta;
+    const float* neg_lse2;   // -LSE * log2(e), from the Delta kernel
+    const float* delta;
     __bf16* dQ; __bf16* dK; __bf16* dV;
     const Item* items; const int32_t* row_lo; const int32_t* row_hi;
     int n_items, n_heads, L;
@@ -29,7 +32,8 @@ __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u 
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
 __global__ __launch_bounds__(256) void hmar_delta_kernel(const __bf16* __restrict__ O, const __bf16* __restrict__ dO,
-                                                         float* __restrict__ delta, long long n_rows) {
+                                                         const float* __restrict__ LSE, float* __restrict__ delta,
+                                                         float* __restrict__ neg_lse2, long long n_rows) {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     const long long row = idx >> 3;
     const int c = (int)(idx & 7);
@@ -43,14 +47,16 @@ __global__ __launch_bounds__(256) void hmar_delta_kernel(const __bf16* __restric
     acc += __shfl_xor(acc, 1);
     acc += __shfl_xor(acc, 2);
     acc += __shfl_xor(acc, 4);
-    if (row < n_rows && c == 0) delta[row] = acc;
+    if (row < n_rows && c == 0) {
+        delta[row] = acc;
+        neg_lse2[row] = -LSE[row] * kLog2e;
+    }
 }
 
 // ------------------------------------------------------------------------------------- dQ
 __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
-    __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTile * kLdRow];
-    __shared__ __attribute__((aligned(16))) __bf16 Vs[2][kTile * kLdRow];
-    __shared__ __attribute__((aligned(16))) __bf16 Kt[2][kD * kLdTr];
+    __shared__ __attribute__((aligned(1024))) char Ks[kStages][kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char Vs[kStages][kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -60,6 +66,7 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
     const size_t head_off = (size_t)head * p.L * kD;
     const __bf16* Kh = p.K + head_off;
     const __bf16* Vh = p.V + head_off;
+    const LaneOffsets lo_ = make_lane_offsets(lane, wave);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;
@@ -75,7 +82,7 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
         q[t] = *reinterpret_cast<const bf16x8*>(p.Q + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
         dob[t] = *reinterpret_cast<const bf16x8*>(p.dO + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
     }
-    const float lse2 = p.LSE[(size_t)head * p.L + qrow] * kLog2e;
+    const float nl2 = p.neg_lse2[(size_t)head * p.L + qrow];
     const float delta = p.delta[(size_t)head * p.L + qrow];
 
     f32x16 dq[2];
@@ -87,27 +94,29 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
     const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
     const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
 
-    RowRegs kr, vr;
-    TrRegs ktr;
-    load_rows(kr, Kh, k_begin, kmax, tid);
-    load_rows(vr, Vh, k_begin, kmax, tid);
-    load_tr(ktr, Kh, k_begin, kmax, tid);
-    store_rows(kr, Ks[0], tid);
-    store_rows(vr, Vs[0], tid);
-    store_tr(ktr, Kt[0], tid);
-    __syncthreads();
+    auto issue = [&](int ti) {       // 4 DMA loads per lane and tile
+        const int st = ti % kStages;
+        dma_tile(Kh, k_begin + ti * kTile, kmax, Ks[st], lo_, lane, wave);
+        dma_tile(Vh, k_begin + ti * kTile, kmax, Vs[st], lo_, lane, wave);
+    };
+    issue(0);
+    if (ntiles > 1) issue(1);
+    // make the compiler wait for these registers here, not inside the loop (see the forward)
+    asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]), "v"(dob[0]), "v"(dob[1]), "v"(dob[2]),
+                 "v"(dob[3]), "v"(nl2), "v"(delta));
+    if (ntiles > 1) { HMAR_WAIT_DMA_AND_BARRIER(4); }
+    else            { HMAR_WAIT_DMA_AND_BARRIER(0); }
 
     for (int ti = 0; ti < ntiles; ++ti) {
         const int kt = k_begin + ti * kTile;
-        const int buf = ti & 1;
-        const bool more = ti + 1 < ntiles;
-        if (more) {
-            load_rows(kr, Kh, kt + kTile, kmax, tid);
-            load_rows(vr, Vh, kt + kTile, kmax, tid);
-            load_tr(ktr, Kh, kt + kTile, kmax, tid);
-        }
+        const bool ahead = ti + 2 < ntiles;
+        if (ahead) issue(ti + 2);
         if (wave_active && kt < whi && kt + kTile > wlo) {
+            const char* Kt = Ks[ti % kStages];
+            const char* Vt = Vs[ti % kStages];
             const bool need_mask = kt < full_lo || kt + kTile > full_hi;
+            const unsigned width = (unsigned)(hi - lo);
+            const int rel = kt + 4 * h - lo;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 f32x16 s, dp;
@@ -115,16 +124,19 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
                 for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    s = mfma32(lds_a_row(Ks[buf], 32 * kb + lr, t, h), q[t], s);
-                    dp = mfma32(lds_a_row(Vs[buf], 32 * kb + lr, t, h), dob[t], dp);
+                    s = mfma32(lds_a_row(Kt, lo_, kb, t), q[t], s);
+                    dp = mfma32(lds_a_row(Vt, lo_, kb, t), dob[t], dp);
+                }
+                if (need_mask) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const unsigned j = (unsigned)(rel + 32 * kb + 8 * (i >> 2) + (i & 3));
+                        s[i] = j < width ? s[i] : -INFINITY;     // exp2(-inf) = 0
+                    }
                 }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, -lse2));
-                    if (need_mask) {
-                        const int j = kt + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-                        pv = (j >= lo && j < hi) ? pv : 0.f;
-                    }
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, nl2));
                     s[i] = pv * (dp[i] - delta);
                 }
 #pragma unroll
@@ -134,16 +146,12 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
                                              s[e0 + 4], s[e0 + 5], s[e0 + 6], s[e0 + 7]);
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)
-                        dq[mb] = mfma32(lds_a_tr(Kt[buf], 32 * mb + lr, tp, h), dsb, dq[mb]);
+                        dq[mb] = mfma32(lds_a_tr(Kt, lo_, mb, tp), dsb, dq[mb]);
                 }
             }
         }
-        if (more) {
-            store_rows(kr, Ks[buf ^ 1], tid);
-            store_rows(vr, Vs[buf ^ 1], tid);
-            store_tr(ktr, Kt[buf ^ 1], tid);
-        }
-        __syncthreads();
+        if (ahead) { HMAR_WAIT_DMA_AND_BARRIER(4); }
+        else       { HMAR_WAIT_DMA_AND_BARRIER(0); }
     }
 
     if (wave_active && row_valid) {
@@ -160,12 +168,10 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
 
 // ---------------------------------------------------------------------------------- dK, dV
 __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
-    __shared__ __attribute__((aligned(16))) __bf16 Qs[2][kTile * kLdRow];
-    __shared__ __attribute__((aligned(16))) __bf16 Gs[2][kTile * kLdRow];   // dO rows
-    __shared__ __attribute__((aligned(16))) __bf16 Qt[2][kD * kLdTr];
-    __shared__ __attribute__((aligned(16))) __bf16 Gt[2][kD * kLdTr];      // dO transposed
-    __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
-    __shared__ __attribute__((aligned(16))) float delta_s[2][kTile];
+    __shared__ __attribute__((aligned(1024))) char Qs[kStages][kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char Gs[kStages][kTileBytes];   // dO rows
+    __shared__ __attribute__((aligned(256))) float nl2_s[kStages][kTile];
+    __shared__ __attribute__((aligned(256))) float delta_s[kStages][kTile];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -175,8 +181,9 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
     const size_t head_off = (size_t)head * p.L * kD;
     const __bf16* Qh = p.Q + head_off;
     const __bf16* Gh = p.dO + head_off;
-    const float* LSEh = p.LSE + (size_t)head * p.L;
+    const float* NLh = p.neg_lse2 + (size_t)head * p.L;
     const float* Dh = p.delta + (size_t)head * p.L;
+    const LaneOffsets lo_ = make_lane_offsets(lane, wave);
 
     const int wk0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wk0 < it.own_end;
@@ -202,36 +209,36 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
     const int q_begin = it.other_begin, q_end = it.other_end, qmax = q_end - 1;
     const int ntiles = (q_end - q_begin + kTile - 1) / kTile;
 
-    RowRegs qr, gr;
-    TrRegs qtr, gtr;
-    float stat = 0.f;   // threads 0..63 carry LSE*log2e of row tid, threads 64..127 carry Delta
-    auto load_stage = [&](int qt) {
-        load_rows(qr, Qh, qt, qmax, tid);
-        load_rows(gr, Gh, qt, qmax, tid);
-        load_tr(qtr, Qh, qt, qmax, tid);
-        load_tr(gtr, Gh, qt, qmax, tid);
-        if (tid < 64) stat = LSEh[min(qt + tid, qmax)] * kLog2e;
-        else if (tid < 128) stat = Dh[min(qt + tid - 64, qmax)];
+    // per lane and tile: 4 DMA loads, plus one for wavefronts 0 (-LSE*log2e) and 1 (Delta)
+    auto issue = [&](int ti) {
+        const int st = ti % kStages;
+        const int qt = q_begin + ti * kTile;
+        dma_tile(Qh, qt, qmax, Qs[st], lo_, lane, wave);
+        dma_tile(Gh, qt, qmax, Gs[st], lo_, lane, wave);
+        if (wave == 0) dma_floats(NLh, qt, qmax, nl2_s[st], lane);
+        else if (wave == 1) dma_floats(Dh, qt, qmax, delta_s[st], lane);
     };
-    auto store_stage = [&](int b) {
-        store_rows(qr, Qs[b], tid);
-        store_rows(gr, Gs[b], tid);
-        store_tr(qtr, Qt[b], tid);
-        store_tr(gtr, Gt[b], tid);
-        if (tid < 64) lse_s[b][tid] = stat;
-        else if (tid < 128) delta_s[b][tid - 64] = stat;
-    };
-    load_stage(q_begin);
-    store_stage(0);
-    __syncthreads();
+    issue(0);
+    if (ntiles > 1) issue(1);
+    asm volatile("" :: "v"(kreg[0]), "v"(kreg[1]), "v"(kreg[2]), "v"(kreg[3]), "v"(vreg[0]), "v"(vreg[1]),
+                 "v"(vreg[2]), "v"(vreg[3]));
+    if (ntiles > 1) {
+        if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5); } else { HMAR_WAIT_DMA_AND_BARRIER(4); }
+    } else {
+        HMAR_WAIT_DMA_AND_BARRIER(0);
+    }
 
     for (int ti = 0; ti < ntiles; ++ti) {
         const int qt = q_begin + ti * kTile;
-        const int buf = ti & 1;
-        const bool more = ti + 1 < ntiles;
-        if (more) load_stage(qt + kTile);
+        const bool ahead = ti + 2 < ntiles;
+        if (ahead) issue(ti + 2);
         if (wave_active && qt < whi && qt + kTile > wlo) {
+            const int st = ti % kStages;
+            const char* Qt = Qs[st];
+            const char* Gt = Gs[st];
             const bool need_mask = qt < full_lo || qt + kTile > full_hi;
+            const unsigned width = (unsigned)(hi - lo);
+            const int rel = qt + 4 * h - lo;
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
                 f32x16 s, dp;
@@ -239,21 +246,24 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
                 for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    s = mfma32(lds_a_row(Qs[buf], 32 * qb + lr, t, h), kreg[t], s);
-                    dp = mfma32(lds_a_row(Gs[buf], 32 * qb + lr, t, h), vreg[t], dp);
+                    s = mfma32(lds_a_row(Qt, lo_, qb, t), kreg[t], s);
+                    dp = mfma32(lds_a_row(Gt, lo_, qb, t), vreg[t], dp);
+                }
+                if (need_mask) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const unsigned j = (unsigned)(rel + 32 * qb + 8 * (i >> 2) + (i & 3));
+                        s[i] = j < width ? s[i] : -INFINITY;
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse_s[buf][32 * qb + 8 * j + 4 * h]);
-                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(&delta_s[buf][32 * qb + 8 * j + 4 * h]);
+                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(&nl2_s[st][32 * qb + 8 * j + 4 * h]);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(&delta_s[st][32 * qb + 8 * j + 4 * h]);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int i = 4 * j + r;
-                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, -l4[r]));
-                        if (need_mask) {
-                            const int qi = qt + 32 * qb + 8 * j + 4 * h + r;
-                            pv = (qi >= lo && qi < hi) ? pv : 0.f;
-                        }
+                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, l4[r]));
                         s[i] = pv;
                         dp[i] = pv * (dp[i] - d4[r]);
                     }
@@ -267,14 +277,17 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
                                              dp[e0 + 4], dp[e0 + 5], dp[e0 + 6], dp[e0 + 7]);
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb) {
-                        dv[mb] = mfma32(lds_a_tr(Gt[buf], 32 * mb + lr, tp, h), pb, dv[mb]);
-                        dk[mb] = mfma32(lds_a_tr(Qt[buf], 32 * mb + lr, tp, h), dsb, dk[mb]);
+                        dv[mb] = mfma32(lds_a_tr(Gt, lo_, mb, tp), pb, dv[mb]);
+                        dk[mb] = mfma32(lds_a_tr(Qt, lo_, mb, tp), dsb, dk[mb]);
                     }
                 }
             }
         }
-        if (more) store_stage(buf ^ 1);
-        __syncthreads();
+        if (ahead) {
+            if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5); } else { HMAR_WAIT_DMA_AND_BARRIER(4); }
+        } else {
+            HMAR_WAIT_DMA_AND_BARRIER(0);
+        }
     }
 
     if (wave_active && row_valid) {
@@ -294,14 +307,16 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
 }
 
 hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
-                      const float* LSE, void* dQ, void* dK, void* dV, float* delta,
+                      const float* LSE, void* dQ, void* dK, void* dV, float* workspace,
                       const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream) {
     const long long n_rows = (long long)n_heads * s.L;
     const long long dgroups = (n_rows * 8 + 255) / 256;
     if (dgroups <= 0 || dgroups > 0x7fffffffLL) return hipErrorInvalidValue;
+    float* delta = workspace;
+    float* neg_lse2 = workspace + n_rows;
     profile_before(kKernelDelta, stream);
     hipLaunchKernelGGL(hmar_delta_kernel, dim3((unsigned)dgroups), dim3(256), 0, stream,
-                       static_cast<const __bf16*>(O), static_cast<const __bf16*>(dO), delta, n_rows);
+                       static_cast<const __bf16*>(O), static_cast<const __bf16*>(dO), LSE, delta, neg_lse2, n_rows);
     hipError_t e = hipGetLastError();
     profile_after(kKernelDelta, stream);
     if (e != hipSuccess) return e;
@@ -311,7 +326,7 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
     p.K = static_cast<const __bf16*>(K);
     p.V = static_cast<const __bf16*>(V);
     p.dO = static_cast<const __bf16*>(dO);
-    p.LSE = LSE;
+    p.neg_lse2 = neg_lse2;
     p.delta = delta;
     p.dQ = static_cast<__bf16*>(dQ);
     p.dK = static_cast<__bf16*>(dK);

@@ -2,14 +2,26 @@
 //
 // MFMA register layouts used throughout (v_mfma_f32_32x32x16_bf16, wave64), with
 // lr = lane % 32 and h = lane / 32:
-//   A operand (M x 16): lane holds row lr, 8 consecutive k of half h (k = 8h .. 8h+7)
-//   B operand (16 x N): lane holds column lr, the same 8 k
+//   A operand (M x 16): lane holds row lr, 8 k-values of half h
+//   B operand (16 x N): lane holds column lr, the same 8 k-values
 //   C/D      (M x N)  : lane holds column lr; register i holds row 8*(i/4) + 4*h + i%4
 // The contraction index only has to be enumerated identically by A and B, so a C tile
 // can be fed back as a B operand without moving data between lanes: registers 8s..8s+7
-// of a C tile (s = 0, 1) are "k = 0..7 of half h" of a 16-deep step whose k-th row is
-// row 16s + 8*(k/4) + 4h + k%4 of the tile; the A operand is then read from LDS with the
-// same row enumeration (two 4-element groups, 8 rows apart).
+// of a C tile (s = 0, 1) are the 8 k-values of half h of a 16-deep step whose rows are
+//   16s + 4h + {0,1,2,3}  and  16s + 8 + 4h + {0,1,2,3}
+// of the tile.  The matching A operand is fetched with the LDS transpose load
+// (ds_read_b64_tr_b16): within a group of 16 lanes, lane i supplies the address of 4
+// consecutive elements of row i/4, columns 4*(i%4).., of a 4 x 16 block, and receives
+// column i of that block (4 rows).  Two such loads give the 8 k-values above.
+//
+// LDS tiles are 64 rows x 64 bf16, row-major, 128 bytes per row, no padding.  The eight
+// 16-byte chunks of row r are stored permuted: chunk c lives at chunk position
+// c ^ swz(r).  The permutation keeps (a) the row-wise 16-byte operand reads of 16
+// consecutive rows and (b) the transpose loads of 4 consecutive rows on distinct banks.
+// Tiles are filled by global->LDS DMA loads (global_load_lds_dwordx4): a wavefront writes
+// 1 KB = 8 rows contiguously, so each lane fetches the global chunk that belongs at its
+// own LDS position; the permutation stays inside a 128-byte row, so the global side
+// remains fully coalesced.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -19,24 +31,29 @@ namespace hmar {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // plain vector types: HIP's uint4/uint2
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;   // structs copy through memory
 
-constexpr int kD = 64;        // head dimension
-constexpr int kTile = 64;     // streamed rows per LDS tile
-constexpr int kLdRow = 72;    // pitch (bf16) of a row-major [rows][64] tile: 64 + 8 pad, 144 B
-constexpr int kLdTr = 68;     // pitch (bf16) of a transposed [64 d][rows] tile: 64 + 4 pad, 136 B
-constexpr int kThreads = 256; // 4 wavefronts
+constexpr int kD = 64;            // head dimension
+constexpr int kTile = 64;         // streamed rows per LDS tile
+constexpr int kRowBytes = 128;    // one bf16 row of the head dimension
+constexpr int kTileBytes = kTile * kRowBytes;   // 8 KB
+constexpr int kThreads = 256;     // 4 wavefronts
 constexpr int kRowsPerWave = 32;
-constexpr int kRowsPerItem = 128;
+constexpr int kStages = 3;        // LDS ring: loads run two tiles ahead of the compute
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;
 
 struct alignas(16) Item { int32_t own_begin, own_end, other_begin, other_end; };
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
 
 // Workgroup -> (head, item).  Workgroups are handed to the 8 XCDs round-robin, so all
 // items of one head are given ids that are congruent mod 8: they then run on one XCD and
@@ -90,63 +107,110 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
     return __builtin_bit_cast(bf16x8, u);
 }
 
-// ---- staging of one 64-row tile of a [rows][64] bf16 matrix into LDS --------------------
-// row-major copy: thread t moves rows t/8 and 32 + t/8, 16-byte column chunk t%8
-struct RowRegs { u32x4 a, b; };
-__device__ __forceinline__ void load_rows(RowRegs& r, const __bf16* base, int row0, int row_max, int tid) {
-    const int rr = tid >> 3, c = tid & 7;
-    const int a = min(row0 + rr, row_max), b = min(row0 + 32 + rr, row_max);
-    r.a = *reinterpret_cast<const u32x4*>(base + (size_t)a * kD + c * 8);
-    r.b = *reinterpret_cast<const u32x4*>(base + (size_t)b * kD + c * 8);
-}
-__device__ __forceinline__ void store_rows(const RowRegs& r, __bf16* lds, int tid) {
-    const int rr = tid >> 3, c = tid & 7;
-    *reinterpret_cast<u32x4*>(lds + rr * kLdRow + c * 8) = r.a;
-    *reinterpret_cast<u32x4*>(lds + (rr + 32) * kLdRow + c * 8) = r.b;
+// ---- LDS tile layout --------------------------------------------------------------------
+// chunk permutation of row r: depends on (r >> 1) & 7 only
+__device__ __forceinline__ int swz(int r) {
+    const int u = (r >> 1) & 7;
+    return ((u & 1) << 2) | (u >> 1);
 }
 
-// transposed copy: thread t moves rows 4*(t/16) .. +3, 4-column chunk t%16, and writes the
-// 4x4 block transposed (4 rows of one column packed in 8 bytes) into a [64 col][rows] tile
-struct TrRegs { u32x2 v0, v1, v2, v3; };
-__device__ __forceinline__ void load_tr(TrRegs& r, const __bf16* base, int row0, int row_max, int tid) {
-    const int c = tid & 15, g = tid >> 4;
-    const int r0 = row0 + 4 * g;
-    r.v0 = *reinterpret_cast<const u32x2*>(base + (size_t)min(r0 + 0, row_max) * kD + c * 4);
-    r.v1 = *reinterpret_cast<const u32x2*>(base + (size_t)min(r0 + 1, row_max) * kD + c * 4);
-    r.v2 = *reinterpret_cast<const u32x2*>(base + (size_t)min(r0 + 2, row_max) * kD + c * 4);
-    r.v3 = *reinterpret_cast<const u32x2*>(base + (size_t)min(r0 + 3, row_max) * kD + c * 4);
-}
-__device__ __forceinline__ void store_tr(const TrRegs& r, __bf16* lds, int tid) {
-    const int c = tid & 15, g = tid >> 4;
-    constexpr uint32_t kLo = 0x05040100u, kHi = 0x07060302u;
-    u32x2 w;
-    __bf16* dst = lds + (4 * c) * kLdTr + 4 * g;
-    w.x = __builtin_amdgcn_perm(r.v1.x, r.v0.x, kLo);
-    w.y = __builtin_amdgcn_perm(r.v3.x, r.v2.x, kLo);
-    *reinterpret_cast<u32x2*>(dst) = w;
-    w.x = __builtin_amdgcn_perm(r.v1.x, r.v0.x, kHi);
-    w.y = __builtin_amdgcn_perm(r.v3.x, r.v2.x, kHi);
-    *reinterpret_cast<u32x2*>(dst + kLdTr) = w;
-    w.x = __builtin_amdgcn_perm(r.v1.y, r.v0.y, kLo);
-    w.y = __builtin_amdgcn_perm(r.v3.y, r.v2.y, kLo);
-    *reinterpret_cast<u32x2*>(dst + 2 * kLdTr) = w;
-    w.x = __builtin_amdgcn_perm(r.v1.y, r.v0.y, kHi);
-    w.y = __builtin_amdgcn_perm(r.v3.y, r.v2.y, kHi);
-    *reinterpret_cast<u32x2*>(dst + 3 * kLdTr) = w;
+// Per-lane byte offsets into a tile, computed once per kernel.
+struct LaneOffsets {
+    int row0, row1, row2, row3;   // row-wise A operand: row lr (+32 per block), 16-byte chunk 2t + h
+    int trA0, trA1;               // transpose load, rows 4h + i/4 of a 16-row step, column block 0 / 1
+    int trB0, trB1;               // the same, 8 rows further down
+    int dma_src;                  // byte offset, inside its 128-byte global row, of the 16 bytes
+                                  // this lane moves (row = lane/8 of the 8 rows a wavefront writes)
+};
+
+__device__ __forceinline__ LaneOffsets make_lane_offsets(int lane, int wave) {
+    LaneOffsets o;
+    const int lr = lane & 31, h = lane >> 5, i = lane & 15, half16 = (lane >> 4) & 1;
+    const int s = swz(lr);
+    o.row0 = lr * kRowBytes + (((0 + h) ^ s) << 4);
+    o.row1 = lr * kRowBytes + (((2 + h) ^ s) << 4);
+    o.row2 = lr * kRowBytes + (((4 + h) ^ s) << 4);
+    o.row3 = lr * kRowBytes + (((6 + h) ^ s) << 4);
+    const int rA = 4 * h + (i >> 2), rB = rA + 8;
+    const int chunk = 2 * half16 + ((i & 3) >> 1);
+    o.trA0 = rA * kRowBytes + ((chunk ^ swz(rA)) << 4) + 8 * (i & 1);
+    o.trA1 = rA * kRowBytes + (((4 + chunk) ^ swz(rA)) << 4) + 8 * (i & 1);
+    o.trB0 = rB * kRowBytes + ((chunk ^ swz(rB)) << 4) + 8 * (i & 1);
+    o.trB1 = rB * kRowBytes + (((4 + chunk) ^ swz(rB)) << 4) + 8 * (i & 1);
+    // DMA: lane p of a wavefront lands at byte 16p of an 8-row block: row p/8, position p%8.
+    // The block index is wave + 4j (j = 0, 1); swz of row 8*blk + p/8 depends on
+    // (4*blk + p/16) mod 8, i.e. on the parity of blk = parity of wave: one offset serves both j.
+    const int r = 8 * wave + (lane >> 3);
+    o.dma_src = ((lane & 7) ^ swz(r)) << 4;
+    return o;
 }
 
-// A operand from a row-major tile: row `row`, columns 16*t + 8*h .. +7
-__device__ __forceinline__ bf16x8 lds_a_row(const __bf16* tile, int row, int t, int h) {
-    return *reinterpret_cast<const bf16x8*>(tile + row * kLdRow + 16 * t + 8 * h);
+// One global->LDS DMA load: every lane moves BYTES (16 or 4) from its own global address to
+// LDS address lds_base + lane * BYTES; lds_base must be uniform over the wavefront (it goes
+// through M0).  Written as inline assembly so that the compiler does not serialise the LDS
+// reads of the tile being computed behind the loads that run ahead into other tiles;
+// completion is awaited explicitly (wait_dma_and_barrier) before any wavefront reads the tile.
+__device__ __forceinline__ void dma16(const void* src, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(src), "s"(lds_base) : "m0", "memory");
 }
-// A operand from a transposed tile for 16-deep step tp: row `col` of the transposed tile,
-// tile rows 16tp+4h..+3 and 16tp+8+4h..+3 (the enumeration a C tile fed back as B uses)
-__device__ __forceinline__ bf16x8 lds_a_tr(const __bf16* tile, int col, int tp, int h) {
-    const __bf16* p = tile + col * kLdTr + 16 * tp + 4 * h;
-    u32x2 lo = *reinterpret_cast<const u32x2*>(p);
-    u32x2 hi = *reinterpret_cast<const u32x2*>(p + 8);
-    u32x4 u = {lo.x, lo.y, hi.x, hi.y};
-    return __builtin_bit_cast(bf16x8, u);
+__device__ __forceinline__ void dma4(const void* src, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :: "v"(src), "s"(lds_base) : "m0", "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+// Issue the DMA loads of one 64-row tile: rows row0 .. row0+63 of a [rows][64] bf16 matrix
+// (clamped to row_max, so the tail re-reads a valid row), into `tile` (wave-uniform).
+// Two loads per lane.
+__device__ __forceinline__ void dma_tile(const __bf16* base, int row0, int row_max, const char* tile,
+                                         const LaneOffsets& o, int lane, int wave) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int blk = wave + 4 * j;
+        const int r = min(row0 + 8 * blk + (lane >> 3), row_max);
+        const char* src = reinterpret_cast<const char*>(base) + (size_t)r * kRowBytes + o.dma_src;
+        dma16(src, __builtin_amdgcn_readfirstlane(lds_address(tile) + blk * 1024));
+    }
+}
+
+// 64 consecutive fp32 (index clamped to i_max) into `dst` (wave-uniform): one 4-byte DMA
+// load per lane
+__device__ __forceinline__ void dma_floats(const float* base, int i0, int i_max, const float* dst, int lane) {
+    dma4(base + min(i0 + lane, i_max), __builtin_amdgcn_readfirstlane(lds_address(dst)));
+}
+
+// Wait until at most N (<= 15) of this wavefront's DMA loads are outstanding and all its LDS
+// traffic is done, then meet the workgroup.  (A plain __syncthreads() would wait for every
+// outstanding load and so stall the loads running ahead.)  s_waitcnt immediate on gfx9:
+// vmcnt in bits 3:0 (and 15:14), expcnt in 6:4 (7 = no wait), lgkmcnt in 11:8.
+template <int N>
+__device__ __forceinline__ void wait_dma_and_barrier() {
+    static_assert(N >= 0 && N <= 15, "vmcnt immediate");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(N | (7 << 4));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+#define HMAR_WAIT_DMA_AND_BARRIER(N) wait_dma_and_barrier<N>()
+
+// A operand, row-wise: row 32*blk + lr of the tile, columns 16t + 8h .. +7
+__device__ __forceinline__ bf16x8 lds_a_row(const char* tile, const LaneOffsets& o, int blk, int t) {
+    const int off = t == 0 ? o.row0 : t == 1 ? o.row1 : t == 2 ? o.row2 : o.row3;
+    return *reinterpret_cast<const bf16x8*>(tile + blk * (32 * kRowBytes) + off);
+}
+
+// A operand, transposed: column 32*mb + lr of the tile, tile rows of 16-deep step tp in the
+// enumeration a C tile fed back as B uses
+__device__ __forceinline__ bf16x8 lds_a_tr(const char* tile, const LaneOffsets& o, int mb, int tp) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const char* base = tile + tp * (16 * kRowBytes);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (mb ? o.trA1 : o.trA0)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (mb ? o.trB1 : o.trB0)));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
 }
 
 // store 4 consecutive fp32 of one output row as bf16 (8 bytes)

@@ -1,11 +1,13 @@
 // Forward kernel of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
 //
 // One workgroup (4 wavefronts) owns up to 128 consecutive query rows, 32 per wavefront,
-// and streams the key/value rows of their two-scale windows through LDS in tiles of 64.
+// and streams the key/value rows of their two-scale windows through a 3-deep ring of LDS
+// tiles (64 rows each) filled by global->LDS DMA loads that run two tiles ahead.
 // Scores are computed transposed (S^T = K Q^T) so that a lane holds one query column:
 // the row maximum and sum are then lane-local apart from one exchange between the two
 // half-waves, and the probability tile is already laid out as the B operand of the
-// second contraction O^T += V^T P^T.  V tiles are transposed on their way into LDS.
+// second contraction O^T += V^T P^T, whose A operand comes from the row-major V tile
+// through the LDS transpose load.
 #include "device_common.h"
 #include "kernels.h"
 
@@ -26,8 +28,8 @@ struct FwdParams {
 constexpr float kRescaleThreshold = 8.0f;
 
 __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
-    __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTile * kLdRow];
-    __shared__ __attribute__((aligned(16))) __bf16 Vt[2][kD * kLdTr];
+    __shared__ __attribute__((aligned(1024))) char Ks[kStages][kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char Vs[kStages][kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -38,6 +40,7 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
     const __bf16* Qh = p.Q + head_off;
     const __bf16* Kh = p.K + head_off;
     const __bf16* Vh = p.V + head_off;
+    const LaneOffsets lo_ = make_lane_offsets(lane, wave);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;               // uniform over the wavefront
@@ -62,25 +65,30 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
     const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
     const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
 
-    RowRegs kr;
-    TrRegs vr;
-    load_rows(kr, Kh, k_begin, kmax, tid);
-    load_tr(vr, Vh, k_begin, kmax, tid);
-    store_rows(kr, Ks[0], tid);
-    store_tr(vr, Vt[0], tid);
-    __syncthreads();
+    // 4 DMA loads per lane and tile (2 for K, 2 for V)
+    auto issue = [&](int ti) {
+        const int st = ti % kStages;
+        dma_tile(Kh, k_begin + ti * kTile, kmax, Ks[st], lo_, lane, wave);
+        dma_tile(Vh, k_begin + ti * kTile, kmax, Vs[st], lo_, lane, wave);
+    };
+    issue(0);
+    if (ntiles > 1) issue(1);
+    // The compiler does not see the DMA loads; without this use it would wait for the Q
+    // registers inside the loop, where its count would also drain the loads running ahead.
+    asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]));
+    if (ntiles > 1) {
+        HMAR_WAIT_DMA_AND_BARRIER(4);     // tile 0 has landed; tile 1 may still be in flight
+    } else {
+        HMAR_WAIT_DMA_AND_BARRIER(0);
+    }
 
     for (int ti = 0; ti < ntiles; ++ti) {
         const int kt = k_begin + ti * kTile;
-        const int buf = ti & 1;
-        const bool more = ti + 1 < ntiles;
-        if (more) {
-            load_rows(kr, Kh, kt + kTile, kmax, tid);
-            load_tr(vr, Vh, kt + kTile, kmax, tid);
-        }
+        const bool ahead = ti + 2 < ntiles;
+        if (ahead) issue(ti + 2);          // into the stage every wave left at the last barrier
         if (wave_active && kt < whi && kt + kTile > wlo) {
-            const __bf16* Kt = Ks[buf];
-            const __bf16* Vtt = Vt[buf];
+            const char* Kt = Ks[ti % kStages];
+            const char* Vt = Vs[ti % kStages];
             f32x16 s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -88,16 +96,18 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
                 for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    s[kb] = mfma32(lds_a_row(Kt, 32 * kb + lr, t, h), q[t], s[kb]);
+                    s[kb] = mfma32(lds_a_row(Kt, lo_, kb, t), q[t], s[kb]);
             }
             if (kt < full_lo || kt + kTile > full_hi) {
                 // tile straddles a window edge of some row: mask per element
+                const unsigned width = (unsigned)(hi - lo);
+                const int rel = kt + 4 * h - lo;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const int j = kt + 32 * kb + 8 * (i >> 2) + 4 * h + (i & 3);
-                        s[kb][i] = (j >= lo && j < hi) ? s[kb][i] : -INFINITY;
+                        const unsigned j = (unsigned)(rel + 32 * kb + 8 * (i >> 2) + (i & 3));
+                        s[kb][i] = j < width ? s[kb][i] : -INFINITY;
                     }
             }
             float mt = s[0][0];
@@ -132,14 +142,11 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
                                         s[kb][e0 + 4], s[kb][e0 + 5], s[kb][e0 + 6], s[kb][e0 + 7]);
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
-                    o[mb] = mfma32(lds_a_tr(Vtt, 32 * mb + lr, tp, h), pb, o[mb]);
+                    o[mb] = mfma32(lds_a_tr(Vt, lo_, mb, tp), pb, o[mb]);
             }
         }
-        if (more) {
-            store_rows(kr, Ks[buf ^ 1], tid);
-            store_tr(vr, Vt[buf ^ 1], tid);
-        }
-        __syncthreads();
+        if (ahead) { HMAR_WAIT_DMA_AND_BARRIER(4); }   // tile ti+1 landed, tile ti+2 in flight
+        else       { HMAR_WAIT_DMA_AND_BARRIER(0); }
     }
 
     if (wave_active) {

@@ -23,7 +23,7 @@ hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, floa
                       const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream);
 
 hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
-                      const float* LSE, void* dQ, void* dK, void* dV, float* delta,
+                      const float* LSE, void* dQ, void* dK, void* dV, float* workspace,
                       const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream);
 
 }  // namespace hmar

@@ -174,7 +174,9 @@ def test_custom_softmax_scale():
     Q, K, V, dO = si.draw((B, H, L, D), seed=8, n_tensors=4)
     res = _gpu_run(Q, K, V, dO, sides, 0.3)
     heads = _all_heads(B, H)
-    _compare(res, _oracle_heads(Q, K, V, dO, sides, 0.3, heads), heads, "scale0.3")
+    ref = _oracle_heads(Q, K, V, dO, sides, 0.3, heads)
+    # scores have standard deviation 0.3 * 8 = 2.4: peaked softmaxes, gradients at the derived bound
+    _compare(res, ref, heads, "scale0.3", grad_bounds=_operand_rounding_bounds(Q, K, V, dO, sides, 0.3, heads, ref))
 
 
 def test_results_are_deterministic_and_inputs_untouched():

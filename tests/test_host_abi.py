@@ -117,7 +117,7 @@ def test_backward_rejects_bad_arguments_and_small_workspace():
     sides = (1, 2, 3, 4)
     arr = (ctypes.c_int32 * 4)(*sides)
     need = hm.hmar_attn_bwd_workspace_bytes(sides, 2, 2, 64)
-    assert need == 2 * 2 * 30 * 4
+    assert need == 2 * (2 * 2 * 30 * 4)
     assert hm.hmar_attn_bwd_workspace_bytes(sides, 2, 2, 128) == 0
     p = [0x1000 * (i + 1) for i in range(9)]
 
