@@ -98,6 +98,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch the plain copy kernel (for rocprofv3 --pmc traffic calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path shards over (batch, head) without communication; "
@@ -140,6 +142,16 @@ def main() -> int:
         s = sets[i % len(sets)]
         fwd(s)
         bwd(s)
+
+    if args.calibration_copy:
+        # a plain copy kernel of known size (256 MiB read + 256 MiB written per launch): the
+        # reference against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            hm.hmar_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)

@@ -104,6 +104,12 @@ hmar_status hmar_schedule_tiles(const int32_t* side_lens, int32_t num_scales, in
 hmar_status hmar_profile_begin(void);
 hmar_status hmar_profile_end(double* total_ms_out, int64_t* launches_out);
 
+/* Measurement aid: a plain device-to-device copy kernel of `bytes` bytes (a multiple of 16;
+ * dst and src device pointers, 16-byte aligned, not overlapping) on `stream`.  Its known
+ * traffic (bytes read + bytes written) calibrates the HBM byte counters read with
+ * rocprofv3 for the attention kernels. */
+hmar_status hmar_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,6 +52,8 @@ def load_library() -> ctypes.CDLL:
     lib.hmar_profile_begin.argtypes = []
     lib.hmar_profile_end.restype = ctypes.c_int
     lib.hmar_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.hmar_calibration_copy.restype = ctypes.c_int
+    lib.hmar_calibration_copy.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -181,3 +183,12 @@ def hmar_profile_end():
     n = (ctypes.c_int64 * 4)()
     _check(load_library().hmar_profile_end(ms, n), "hmar_profile_end")
     return {KERNEL_NAMES[i]: (float(ms[i]), int(n[i])) for i in range(4)}
+
+
+def hmar_calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain device copy kernel of known size (calibrates rocprofv3's HBM byte counters)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (dst.is_cuda and src.is_cuda):
+        raise HmarError("calibration copy needs two device tensors of equal byte size")
+    _check(load_library().hmar_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(src)),
+           "hmar_calibration_copy")

@@ -222,6 +222,11 @@ hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const voi
     return e == hipSuccess ? HMAR_OK : HMAR_ERR_HIP;
 }
 
+hmar_status hmar_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || (bytes & 15u) || !aligned16(dst) || !aligned16(src)) return HMAR_ERR_INVALID_ARG;
+    return hmar::launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? HMAR_OK : HMAR_ERR_HIP;
+}
+
 hmar_status hmar_schedule_describe(const int32_t* side_lens, int32_t num_scales,
                                    int32_t* offsets_out, int64_t* allowed_pairs_out) {
     hmar::Schedule host;

@@ -55,8 +55,8 @@ __global__ __launch_bounds__(256) void hmar_delta_kernel(const __bf16* __restric
 
 // ------------------------------------------------------------------------------------- dQ
 __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
-    __shared__ __attribute__((aligned(1024))) char Ks[kStages][kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char Vs[kStages][kTileBytes];
+    // ring of kStages stages, each a K tile followed by a V tile
+    __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -67,6 +67,18 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
     const __bf16* Kh = p.K + head_off;
     const __bf16* Vh = p.V + head_off;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
+    const uint32_t smem_base = lds_address(smem);
+
+    const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
+    const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
+
+    auto issue = [&](int ti, int st) {       // 4 DMA loads per lane and tile
+        const uint32_t stage = smem_base + st * (2 * kTileBytes);
+        dma_tile(Kh, k_begin + ti * kTile, kmax, stage, lo_, lane, wave);
+        dma_tile(Vh, k_begin + ti * kTile, kmax, stage + kTileBytes, lo_, lane, wave);
+    };
+    issue(0, 0);
+    if (ntiles > 1) issue(1, 1);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;
@@ -91,29 +103,20 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) dq[mb][i] = 0.f;
 
-    const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
-    const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
-
-    auto issue = [&](int ti) {       // 4 DMA loads per lane and tile
-        const int st = ti % kStages;
-        dma_tile(Kh, k_begin + ti * kTile, kmax, Ks[st], lo_, lane, wave);
-        dma_tile(Vh, k_begin + ti * kTile, kmax, Vs[st], lo_, lane, wave);
-    };
-    issue(0);
-    if (ntiles > 1) issue(1);
-    // make the compiler wait for these registers here, not inside the loop (see the forward)
+    // make the compiler wait for these registers here, not inside the loop (see the forward);
+    // loads complete in order, so tiles 0 and 1 have landed as well
     asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]), "v"(dob[0]), "v"(dob[1]), "v"(dob[2]),
                  "v"(dob[3]), "v"(nl2), "v"(delta));
-    if (ntiles > 1) { HMAR_WAIT_DMA_AND_BARRIER(4); }
-    else            { HMAR_WAIT_DMA_AND_BARRIER(0); }
+    HMAR_WAIT_DMA_AND_BARRIER(0);
 
+    int st = 0;
     for (int ti = 0; ti < ntiles; ++ti) {
         const int kt = k_begin + ti * kTile;
         const bool ahead = ti + 2 < ntiles;
-        if (ahead) issue(ti + 2);
+        if (ahead) issue(ti + 2, st >= 1 ? st - 1 : kStages - 1);
         if (wave_active && kt < whi && kt + kTile > wlo) {
-            const char* Kt = Ks[ti % kStages];
-            const char* Vt = Vs[ti % kStages];
+            const uint32_t Kt = smem_base + st * (2 * kTileBytes);
+            const uint32_t Vt = Kt + kTileBytes;
             const bool need_mask = kt < full_lo || kt + kTile > full_hi;
             const unsigned width = (unsigned)(hi - lo);
             const int rel = kt + 4 * h - lo;
@@ -152,6 +155,7 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
         }
         if (ahead) { HMAR_WAIT_DMA_AND_BARRIER(4); }
         else       { HMAR_WAIT_DMA_AND_BARRIER(0); }
+        st = st + 1 == kStages ? 0 : st + 1;
     }
 
     if (wave_active && row_valid) {
@@ -167,9 +171,14 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------- dK, dV
-__global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
-    __shared__ __attribute__((aligned(1024))) char Qs[kStages][kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char Gs[kStages][kTileBytes];   // dO rows
+// Register budget: 3 wavefronts per SIMD (168 VGPRs) hides more latency than 2 with a
+// roomier allocation; measured on the 256px training shape.
+#ifndef HMAR_DKDV_MIN_WAVES
+#define HMAR_DKDV_MIN_WAVES 3
+#endif
+__global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kernel(BwdParams p) {
+    // ring of kStages stages, each a Q tile followed by a dO tile; then the per-row statistics
+    __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
     __shared__ __attribute__((aligned(256))) float nl2_s[kStages][kTile];
     __shared__ __attribute__((aligned(256))) float delta_s[kStages][kTile];
 
@@ -184,6 +193,23 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
     const float* NLh = p.neg_lse2 + (size_t)head * p.L;
     const float* Dh = p.delta + (size_t)head * p.L;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
+    const uint32_t smem_base = lds_address(smem);
+    const uint32_t nl2_base = lds_address(nl2_s), delta_base = lds_address(delta_s);
+
+    const int q_begin = it.other_begin, q_end = it.other_end, qmax = q_end - 1;
+    const int ntiles = (q_end - q_begin + kTile - 1) / kTile;
+
+    // per lane and tile: 4 DMA loads, plus one for wavefronts 0 (-LSE*log2e) and 1 (Delta)
+    auto issue = [&](int ti, int st) {
+        const uint32_t stage = smem_base + st * (2 * kTileBytes);
+        const int qt = q_begin + ti * kTile;
+        dma_tile(Qh, qt, qmax, stage, lo_, lane, wave);
+        dma_tile(Gh, qt, qmax, stage + kTileBytes, lo_, lane, wave);
+        if (wave == 0) dma_floats(NLh, qt, qmax, nl2_base + st * (kTile * 4), lane);
+        else if (wave == 1) dma_floats(Dh, qt, qmax, delta_base + st * (kTile * 4), lane);
+    };
+    issue(0, 0);
+    if (ntiles > 1) issue(1, 1);
 
     const int wk0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wk0 < it.own_end;
@@ -206,36 +232,20 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) { dk[mb][i] = 0.f; dv[mb][i] = 0.f; }
 
-    const int q_begin = it.other_begin, q_end = it.other_end, qmax = q_end - 1;
-    const int ntiles = (q_end - q_begin + kTile - 1) / kTile;
-
-    // per lane and tile: 4 DMA loads, plus one for wavefronts 0 (-LSE*log2e) and 1 (Delta)
-    auto issue = [&](int ti) {
-        const int st = ti % kStages;
-        const int qt = q_begin + ti * kTile;
-        dma_tile(Qh, qt, qmax, Qs[st], lo_, lane, wave);
-        dma_tile(Gh, qt, qmax, Gs[st], lo_, lane, wave);
-        if (wave == 0) dma_floats(NLh, qt, qmax, nl2_s[st], lane);
-        else if (wave == 1) dma_floats(Dh, qt, qmax, delta_s[st], lane);
-    };
-    issue(0);
-    if (ntiles > 1) issue(1);
     asm volatile("" :: "v"(kreg[0]), "v"(kreg[1]), "v"(kreg[2]), "v"(kreg[3]), "v"(vreg[0]), "v"(vreg[1]),
                  "v"(vreg[2]), "v"(vreg[3]));
-    if (ntiles > 1) {
-        if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5); } else { HMAR_WAIT_DMA_AND_BARRIER(4); }
-    } else {
-        HMAR_WAIT_DMA_AND_BARRIER(0);
-    }
+    HMAR_WAIT_DMA_AND_BARRIER(0);
 
+    int st = 0;
     for (int ti = 0; ti < ntiles; ++ti) {
         const int qt = q_begin + ti * kTile;
         const bool ahead = ti + 2 < ntiles;
-        if (ahead) issue(ti + 2);
+        if (ahead) issue(ti + 2, st >= 1 ? st - 1 : kStages - 1);
         if (wave_active && qt < whi && qt + kTile > wlo) {
-            const int st = ti % kStages;
-            const char* Qt = Qs[st];
-            const char* Gt = Gs[st];
+            const uint32_t Qt = smem_base + st * (2 * kTileBytes);
+            const uint32_t Gt = Qt + kTileBytes;
+            const uint32_t nl2_t = nl2_base + st * (kTile * 4) + 16 * h;
+            const uint32_t delta_t = delta_base + st * (kTile * 4) + 16 * h;
             const bool need_mask = qt < full_lo || qt + kTile > full_hi;
             const unsigned width = (unsigned)(hi - lo);
             const int rel = qt + 4 * h - lo;
@@ -258,8 +268,9 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(&nl2_s[st][32 * qb + 8 * j + 4 * h]);
-                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(&delta_s[st][32 * qb + 8 * j + 4 * h]);
+                    // statistics of query rows 32qb + 8j + 4h .. +3 of the tile
+                    const f32x4 l4 = *(lds_f32x4*)(nl2_t + (32 * qb + 8 * j) * 4);
+                    const f32x4 d4 = *(lds_f32x4*)(delta_t + (32 * qb + 8 * j) * 4);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int i = 4 * j + r;
@@ -288,6 +299,7 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
         } else {
             HMAR_WAIT_DMA_AND_BARRIER(0);
         }
+        st = st + 1 == kStages ? 0 : st + 1;
     }
 
     if (wave_active && row_valid) {
@@ -304,6 +316,23 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dkdv_kernel(BwdParams p) {
                 store4_bf16(vrow_out + d0, dv[mb][4 * j], dv[mb][4 * j + 1], dv[mb][4 * j + 2], dv[mb][4 * j + 3]);
             }
     }
+}
+
+// Plain copy, 16 bytes per lane, grid-stride: calibration of the HBM traffic counters.
+__global__ __launch_bounds__(256) void hmar_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
+                                                        size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    const size_t want = (n16 + 255) / 256;
+    const unsigned groups = (unsigned)(want < 256 * 64 ? want : 256 * 64);
+    hipLaunchKernelGGL(hmar_copy_kernel, dim3(groups), dim3(256), 0, stream, static_cast<u32x4*>(dst),
+                       static_cast<const u32x4*>(src), n16);
+    return hipGetLastError();
 }
 
 hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,

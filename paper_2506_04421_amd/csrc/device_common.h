@@ -163,23 +163,23 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 }
 
 // Issue the DMA loads of one 64-row tile: rows row0 .. row0+63 of a [rows][64] bf16 matrix
-// (clamped to row_max, so the tail re-reads a valid row), into `tile` (wave-uniform).
-// Two loads per lane.
-__device__ __forceinline__ void dma_tile(const __bf16* base, int row0, int row_max, const char* tile,
+// (clamped to row_max, so the tail re-reads a valid row), into the tile at LDS address
+// `tile` (wave-uniform).  Two loads per lane.
+__device__ __forceinline__ void dma_tile(const __bf16* base, int row0, int row_max, uint32_t tile,
                                          const LaneOffsets& o, int lane, int wave) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int blk = wave + 4 * j;
         const int r = min(row0 + 8 * blk + (lane >> 3), row_max);
         const char* src = reinterpret_cast<const char*>(base) + (size_t)r * kRowBytes + o.dma_src;
-        dma16(src, __builtin_amdgcn_readfirstlane(lds_address(tile) + blk * 1024));
+        dma16(src, __builtin_amdgcn_readfirstlane(tile + blk * 1024));
     }
 }
 
-// 64 consecutive fp32 (index clamped to i_max) into `dst` (wave-uniform): one 4-byte DMA
-// load per lane
-__device__ __forceinline__ void dma_floats(const float* base, int i0, int i_max, const float* dst, int lane) {
-    dma4(base + min(i0 + lane, i_max), __builtin_amdgcn_readfirstlane(lds_address(dst)));
+// 64 consecutive fp32 (index clamped to i_max) to LDS address `dst` (wave-uniform): one
+// 4-byte DMA load per lane
+__device__ __forceinline__ void dma_floats(const float* base, int i0, int i_max, uint32_t dst, int lane) {
+    dma4(base + min(i0 + lane, i_max), __builtin_amdgcn_readfirstlane(dst));
 }
 
 // Wait until at most N (<= 15) of this wavefront's DMA loads are outstanding and all its LDS
@@ -196,21 +196,31 @@ __device__ __forceinline__ void wait_dma_and_barrier() {
 }
 #define HMAR_WAIT_DMA_AND_BARRIER(N) wait_dma_and_barrier<N>()
 
-// A operand, row-wise: row 32*blk + lr of the tile, columns 16t + 8h .. +7
-__device__ __forceinline__ bf16x8 lds_a_row(const char* tile, const LaneOffsets& o, int blk, int t) {
+// LDS is addressed with plain 32-bit byte addresses so that block, step and stage offsets
+// fold into the instructions' immediate offset fields.
+typedef const __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef const __attribute__((address_space(3))) f32x4 lds_f32x4;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// A operand, row-wise: row 32*blk + lr of the tile at LDS address `tile`, columns 16t + 8h .. +7
+__device__ __forceinline__ bf16x8 lds_a_row(uint32_t tile, const LaneOffsets& o, int blk, int t) {
     const int off = t == 0 ? o.row0 : t == 1 ? o.row1 : t == 2 ? o.row2 : o.row3;
-    return *reinterpret_cast<const bf16x8*>(tile + blk * (32 * kRowBytes) + off);
+    return *(lds_bf16x8*)(tile + off + blk * (32 * kRowBytes));
 }
 
 // A operand, transposed: column 32*mb + lr of the tile, tile rows of 16-deep step tp in the
 // enumeration a C tile fed back as B uses
-__device__ __forceinline__ bf16x8 lds_a_tr(const char* tile, const LaneOffsets& o, int mb, int tp) {
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const char* base = tile + tp * (16 * kRowBytes);
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (mb ? o.trA1 : o.trA0)));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (mb ? o.trB1 : o.trB0)));
+__device__ __forceinline__ bf16x8 lds_a_tr(uint32_t tile, const LaneOffsets& o, int mb, int tp) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + (mb ? o.trA1 : o.trA0) + tp * (16 * kRowBytes)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + (mb ? o.trB1 : o.trB0) + tp * (16 * kRowBytes)));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
+}
+
+// sum of the two bf16 halves of a packed pair, added to acc (v_dot2c_f32_bf16 with ones)
+__device__ __forceinline__ float add_pair_bf16(uint32_t packed, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed),
+                                           __builtin_bit_cast(bf16x2, 0x3F803F80u), acc, false);
 }
 
 // store 4 consecutive fp32 of one output row as bf16 (8 bytes)

@@ -28,8 +28,8 @@ struct FwdParams {
 constexpr float kRescaleThreshold = 8.0f;
 
 __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
-    __shared__ __attribute__((aligned(1024))) char Ks[kStages][kTileBytes];
-    __shared__ __attribute__((aligned(1024))) char Vs[kStages][kTileBytes];
+    // ring of kStages stages, each a K tile followed by a V tile
+    __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -41,6 +41,20 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
     const __bf16* Kh = p.K + head_off;
     const __bf16* Vh = p.V + head_off;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
+    const uint32_t smem_base = lds_address(smem);
+
+    const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
+    const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
+
+    // 4 DMA loads per lane and tile (2 for K, 2 for V); the first two tiles are requested
+    // before anything else so that their latency overlaps the rest of the prologue
+    auto issue = [&](int ti, int st) {
+        const uint32_t stage = smem_base + st * (2 * kTileBytes);
+        dma_tile(Kh, k_begin + ti * kTile, kmax, stage, lo_, lane, wave);
+        dma_tile(Vh, k_begin + ti * kTile, kmax, stage + kTileBytes, lo_, lane, wave);
+    };
+    issue(0, 0);
+    if (ntiles > 1) issue(1, 1);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;               // uniform over the wavefront
@@ -62,33 +76,21 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
         for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
     float m_ref = kNegBig, lsum = 0.f;
 
-    const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
-    const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
-
-    // 4 DMA loads per lane and tile (2 for K, 2 for V)
-    auto issue = [&](int ti) {
-        const int st = ti % kStages;
-        dma_tile(Kh, k_begin + ti * kTile, kmax, Ks[st], lo_, lane, wave);
-        dma_tile(Vh, k_begin + ti * kTile, kmax, Vs[st], lo_, lane, wave);
-    };
-    issue(0);
-    if (ntiles > 1) issue(1);
     // The compiler does not see the DMA loads; without this use it would wait for the Q
     // registers inside the loop, where its count would also drain the loads running ahead.
     asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]));
-    if (ntiles > 1) {
-        HMAR_WAIT_DMA_AND_BARRIER(4);     // tile 0 has landed; tile 1 may still be in flight
-    } else {
-        HMAR_WAIT_DMA_AND_BARRIER(0);
-    }
+    // Loads complete in order: the registers above were requested after tiles 0 and 1.
+    HMAR_WAIT_DMA_AND_BARRIER(0);
 
+    int st = 0;                       // stage of tile ti
     for (int ti = 0; ti < ntiles; ++ti) {
         const int kt = k_begin + ti * kTile;
         const bool ahead = ti + 2 < ntiles;
-        if (ahead) issue(ti + 2);          // into the stage every wave left at the last barrier
+        // tile ti+2 goes into the stage every wave left at the last barrier
+        if (ahead) issue(ti + 2, st >= 1 ? st - 1 : kStages - 1);
         if (wave_active && kt < whi && kt + kTile > wlo) {
-            const char* Kt = Ks[ti % kStages];
-            const char* Vt = Vs[ti % kStages];
+            const uint32_t Kt = smem_base + st * (2 * kTileBytes);
+            const uint32_t Vt = Kt + kTileBytes;
             f32x16 s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -147,6 +149,7 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
         }
         if (ahead) { HMAR_WAIT_DMA_AND_BARRIER(4); }   // tile ti+1 landed, tile ti+2 in flight
         else       { HMAR_WAIT_DMA_AND_BARRIER(0); }
+        st = st + 1 == kStages ? 0 : st + 1;
     }
 
     if (wave_active) {

@@ -26,4 +26,6 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
                       const float* LSE, void* dQ, void* dK, void* dV, float* workspace,
                       const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream);
 
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
 }  // namespace hmar
