@@ -54,14 +54,17 @@ __global__ __launch_bounds__(256) void hmar_delta_kernel(const __bf16* __restric
 }
 
 // ------------------------------------------------------------------------------------- dQ
-__global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
+#ifndef HMAR_DQ_MIN_WAVES
+#define HMAR_DQ_MIN_WAVES 2
+#endif
+__global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(BwdParams p) {
     // ring of kStages stages, each a K tile followed by a V tile
     __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
     const Item it = p.items[item_id];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
     const __bf16* Kh = p.K + head_off;
@@ -77,16 +80,19 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
         dma_tile(Kh, k_begin + ti * kTile, kmax, stage, lo_, lane, wave);
         dma_tile(Vh, k_begin + ti * kTile, kmax, stage + kTileBytes, lo_, lane, wave);
     };
-    issue(0, 0);
-    if (ntiles > 1) issue(1, 1);
+#pragma unroll
+    for (int d = 0; d < kAhead; ++d)
+        if (d < ntiles) issue(d, d);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;
     const bool row_valid = wq0 + lr < it.own_end;
     const int qrow = min(wq0 + lr, it.own_end - 1);
     const int lo = p.row_lo[qrow], hi = p.row_hi[qrow];
-    const int wlo = wave_min(lo), whi = wave_max(hi);
-    const int full_lo = wave_max(lo), full_hi = wave_min(hi);
+    // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
+    const int rfirst = min(wq0, it.own_end - 1), rlast = min(wq0 + kRowsPerWave - 1, it.own_end - 1);
+    const int wlo = p.row_lo[rfirst], whi = p.row_hi[rlast];        // union of the wavefront's ranges
+    const int full_lo = p.row_lo[rlast], full_hi = p.row_hi[rfirst];  // what every one of its rows pairs with
 
     bf16x8 q[4], dob[4];
 #pragma unroll
@@ -112,14 +118,13 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
     int st = 0;
     for (int ti = 0; ti < ntiles; ++ti) {
         const int kt = k_begin + ti * kTile;
-        const bool ahead = ti + 2 < ntiles;
-        if (ahead) issue(ti + 2, st >= 1 ? st - 1 : kStages - 1);
+        const bool ahead = ti + kAhead < ntiles;
+        if (ahead) issue(ti + kAhead, st >= 1 ? st - 1 : kStages - 1);
         if (wave_active && kt < whi && kt + kTile > wlo) {
             const uint32_t Kt = smem_base + st * (2 * kTileBytes);
             const uint32_t Vt = Kt + kTileBytes;
-            const bool need_mask = kt < full_lo || kt + kTile > full_hi;
-            const unsigned width = (unsigned)(hi - lo);
-            const int rel = kt + 4 * h - lo;
+            const bool need_lo = kt < full_lo, need_hi = kt + kTile > full_hi;
+            const int lim_lo = lo - kt - 4 * h, lim_hi = hi - kt - 4 * h;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 f32x16 s, dp;
@@ -130,13 +135,7 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
                     s = mfma32(lds_a_row(Kt, lo_, kb, t), q[t], s);
                     dp = mfma32(lds_a_row(Vt, lo_, kb, t), dob[t], dp);
                 }
-                if (need_mask) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const unsigned j = (unsigned)(rel + 32 * kb + 8 * (i >> 2) + (i & 3));
-                        s[i] = j < width ? s[i] : -INFINITY;     // exp2(-inf) = 0
-                    }
-                }
+                mask_block(s, 32 * kb, lim_lo, lim_hi, need_lo, need_hi);     // exp2(-inf) = 0
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, nl2));
@@ -153,8 +152,8 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_dq_kernel(BwdParams p) {
                 }
             }
         }
-        if (ahead) { HMAR_WAIT_DMA_AND_BARRIER(4); }
-        else       { HMAR_WAIT_DMA_AND_BARRIER(0); }
+        if (ahead && kAhead > 1) { HMAR_WAIT_DMA_AND_BARRIER(4 * (kAhead - 1)); }
+        else                     { HMAR_WAIT_DMA_AND_BARRIER(0); }
         st = st + 1 == kStages ? 0 : st + 1;
     }
 
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
     const Item it = p.items[item_id];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
     const __bf16* Qh = p.Q + head_off;
@@ -208,16 +207,19 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
         if (wave == 0) dma_floats(NLh, qt, qmax, nl2_base + st * (kTile * 4), lane);
         else if (wave == 1) dma_floats(Dh, qt, qmax, delta_base + st * (kTile * 4), lane);
     };
-    issue(0, 0);
-    if (ntiles > 1) issue(1, 1);
+#pragma unroll
+    for (int d = 0; d < kAhead; ++d)
+        if (d < ntiles) issue(d, d);
 
     const int wk0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wk0 < it.own_end;
     const bool row_valid = wk0 + lr < it.own_end;
     const int krow = min(wk0 + lr, it.own_end - 1);
     const int lo = p.row_lo[krow], hi = p.row_hi[krow];       // queries that see this key
-    const int wlo = wave_min(lo), whi = wave_max(hi);
-    const int full_lo = wave_max(lo), full_hi = wave_min(hi);
+    // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
+    const int rfirst = min(wk0, it.own_end - 1), rlast = min(wk0 + kRowsPerWave - 1, it.own_end - 1);
+    const int wlo = p.row_lo[rfirst], whi = p.row_hi[rlast];        // union of the wavefront's ranges
+    const int full_lo = p.row_lo[rlast], full_hi = p.row_hi[rfirst];  // what every one of its rows pairs with
 
     bf16x8 kreg[4], vreg[4];
 #pragma unroll
@@ -239,16 +241,15 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
     int st = 0;
     for (int ti = 0; ti < ntiles; ++ti) {
         const int qt = q_begin + ti * kTile;
-        const bool ahead = ti + 2 < ntiles;
-        if (ahead) issue(ti + 2, st >= 1 ? st - 1 : kStages - 1);
+        const bool ahead = ti + kAhead < ntiles;
+        if (ahead) issue(ti + kAhead, st >= 1 ? st - 1 : kStages - 1);
         if (wave_active && qt < whi && qt + kTile > wlo) {
             const uint32_t Qt = smem_base + st * (2 * kTileBytes);
             const uint32_t Gt = Qt + kTileBytes;
             const uint32_t nl2_t = nl2_base + st * (kTile * 4) + 16 * h;
             const uint32_t delta_t = delta_base + st * (kTile * 4) + 16 * h;
-            const bool need_mask = qt < full_lo || qt + kTile > full_hi;
-            const unsigned width = (unsigned)(hi - lo);
-            const int rel = qt + 4 * h - lo;
+            const bool need_lo = qt < full_lo, need_hi = qt + kTile > full_hi;
+            const int lim_lo = lo - qt - 4 * h, lim_hi = hi - qt - 4 * h;
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
                 f32x16 s, dp;
@@ -259,13 +260,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
                     s = mfma32(lds_a_row(Qt, lo_, qb, t), kreg[t], s);
                     dp = mfma32(lds_a_row(Gt, lo_, qb, t), vreg[t], dp);
                 }
-                if (need_mask) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const unsigned j = (unsigned)(rel + 32 * qb + 8 * (i >> 2) + (i & 3));
-                        s[i] = j < width ? s[i] : -INFINITY;
-                    }
-                }
+                mask_block(s, 32 * qb, lim_lo, lim_hi, need_lo, need_hi);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     // statistics of query rows 32qb + 8j + 4h .. +3 of the tile
@@ -294,8 +289,8 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
                 }
             }
         }
-        if (ahead) {
-            if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5); } else { HMAR_WAIT_DMA_AND_BARRIER(4); }
+        if (ahead && kAhead > 1) {
+            if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5 * (kAhead - 1)); } else { HMAR_WAIT_DMA_AND_BARRIER(4 * (kAhead - 1)); }
         } else {
             HMAR_WAIT_DMA_AND_BARRIER(0);
         }

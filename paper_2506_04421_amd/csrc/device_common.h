@@ -45,7 +45,14 @@ constexpr int kRowBytes = 128;    // one bf16 row of the head dimension
 constexpr int kTileBytes = kTile * kRowBytes;   // 8 KB
 constexpr int kThreads = 256;     // 4 wavefronts
 constexpr int kRowsPerWave = 32;
-constexpr int kStages = 3;        // LDS ring: loads run two tiles ahead of the compute
+// Two stages (32 KB per workgroup) measured faster than three or four on the 256px training
+// shape: the LDS saved lets a fourth workgroup live on each CU, and with 3-4 wavefronts per
+// SIMD other workgroups hide the load latency better than a deeper ring does.
+#ifndef HMAR_STAGES
+#define HMAR_STAGES 2
+#endif
+constexpr int kStages = HMAR_STAGES;   // LDS ring depth
+constexpr int kAhead = kStages - 1;    // the DMA loads run this many tiles ahead of the compute
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;
@@ -221,6 +228,23 @@ __device__ __forceinline__ bf16x8 lds_a_tr(uint32_t tile, const LaneOffsets& o, 
 __device__ __forceinline__ float add_pair_bf16(uint32_t packed, float acc) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed),
                                            __builtin_bit_cast(bf16x2, 0x3F803F80u), acc, false);
+}
+
+// Mask one 32 x 32 score block held in the C layout.  Register i of the lane is the
+// streamed row (key in the forward and dQ kernels, query in the dK/dV kernel) with index
+// c0 + 8*(i/4) + i%4 relative to the lane's base row; entries whose relative index lies
+// outside [lim_lo, lim_hi) become -inf (their probability is then exactly 0).  need_lo and
+// need_hi are uniform over the wavefront: only tiles that straddle an edge of some row's
+// range pay for the compare-and-select.
+__device__ __forceinline__ void mask_block(f32x16& s, int c0, int lim_lo, int lim_hi, bool need_lo, bool need_hi) {
+    if (need_hi) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] = (c0 + 8 * (i >> 2) + (i & 3)) < lim_hi ? s[i] : -INFINITY;
+    }
+    if (need_lo) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] = (c0 + 8 * (i >> 2) + (i & 3)) >= lim_lo ? s[i] : -INFINITY;
+    }
 }
 
 // store 4 consecutive fp32 of one output row as bf16 (8 bytes)

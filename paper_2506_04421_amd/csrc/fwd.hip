@@ -27,14 +27,17 @@ struct FwdParams {
 // independent of the reference.
 constexpr float kRescaleThreshold = 8.0f;
 
-__global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
+#ifndef HMAR_FWD_MIN_WAVES
+#define HMAR_FWD_MIN_WAVES 2
+#endif
+__global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(FwdParams p) {
     // ring of kStages stages, each a K tile followed by a V tile
     __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
     const Item it = p.items[item_id];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
     const __bf16* Qh = p.Q + head_off;
@@ -53,16 +56,19 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
         dma_tile(Kh, k_begin + ti * kTile, kmax, stage, lo_, lane, wave);
         dma_tile(Vh, k_begin + ti * kTile, kmax, stage + kTileBytes, lo_, lane, wave);
     };
-    issue(0, 0);
-    if (ntiles > 1) issue(1, 1);
+#pragma unroll
+    for (int d = 0; d < kAhead; ++d)
+        if (d < ntiles) issue(d, d);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;               // uniform over the wavefront
     const bool row_valid = wq0 + lr < it.own_end;
     const int qrow = min(wq0 + lr, it.own_end - 1);
     const int lo = p.row_lo[qrow], hi = p.row_hi[qrow];
-    const int wlo = wave_min(lo), whi = wave_max(hi);        // union of the wave's windows
-    const int full_lo = wave_max(lo), full_hi = wave_min(hi);  // keys every row of the wave sees
+    // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
+    const int rfirst = min(wq0, it.own_end - 1), rlast = min(wq0 + kRowsPerWave - 1, it.own_end - 1);
+    const int wlo = p.row_lo[rfirst], whi = p.row_hi[rlast];        // union of the wavefront's ranges
+    const int full_lo = p.row_lo[rlast], full_hi = p.row_hi[rfirst];  // what every one of its rows pairs with
 
     bf16x8 q[4];
 #pragma unroll
@@ -85,9 +91,9 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
     int st = 0;                       // stage of tile ti
     for (int ti = 0; ti < ntiles; ++ti) {
         const int kt = k_begin + ti * kTile;
-        const bool ahead = ti + 2 < ntiles;
-        // tile ti+2 goes into the stage every wave left at the last barrier
-        if (ahead) issue(ti + 2, st >= 1 ? st - 1 : kStages - 1);
+        const bool ahead = ti + kAhead < ntiles;
+        // the tile kAhead ahead goes into the stage every wave left at the last barrier
+        if (ahead) issue(ti + kAhead, st >= 1 ? st - 1 : kStages - 1);
         if (wave_active && kt < whi && kt + kTile > wlo) {
             const uint32_t Kt = smem_base + st * (2 * kTileBytes);
             const uint32_t Vt = Kt + kTileBytes;
@@ -100,18 +106,10 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
                 for (int t = 0; t < 4; ++t)
                     s[kb] = mfma32(lds_a_row(Kt, lo_, kb, t), q[t], s[kb]);
             }
-            if (kt < full_lo || kt + kTile > full_hi) {
-                // tile straddles a window edge of some row: mask per element
-                const unsigned width = (unsigned)(hi - lo);
-                const int rel = kt + 4 * h - lo;
+            // element i of block kb is key kt + 4h + 32kb + 8(i/4) + i%4; allowed iff lo <= key < hi
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const unsigned j = (unsigned)(rel + 32 * kb + 8 * (i >> 2) + (i & 3));
-                        s[kb][i] = j < width ? s[kb][i] : -INFINITY;
-                    }
-            }
+            for (int kb = 0; kb < 2; ++kb)
+                mask_block(s[kb], 32 * kb, lo - kt - 4 * h, hi - kt - 4 * h, kt < full_lo, kt + kTile > full_hi);
             float mt = s[0][0];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -147,8 +145,9 @@ __global__ __launch_bounds__(kThreads, 2) void hmar_fwd_kernel(FwdParams p) {
                     o[mb] = mfma32(lds_a_tr(Vt, lo_, mb, tp), pb, o[mb]);
             }
         }
-        if (ahead) { HMAR_WAIT_DMA_AND_BARRIER(4); }   // tile ti+1 landed, tile ti+2 in flight
-        else       { HMAR_WAIT_DMA_AND_BARRIER(0); }
+        // tile ti+1 has landed; up to kAhead-1 later tiles (4 loads each) may be in flight
+        if (ahead && kAhead > 1) { HMAR_WAIT_DMA_AND_BARRIER(4 * (kAhead - 1)); }
+        else                     { HMAR_WAIT_DMA_AND_BARRIER(0); }
         st = st + 1 == kStages ? 0 : st + 1;
     }
 

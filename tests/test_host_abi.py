@@ -70,6 +70,9 @@ def test_tile_schedule_covers_exactly_the_mask(sides, which):
         for t in range(ob, oe, 64):
             assert mask[b:e, t:min(t + 64, oe)].any()
     assert (owned == 1).all()
+    # the kernels take a wavefront's extreme ranges from its first and last row: both bounds
+    # must be non-decreasing along the rows
+    assert all(lo[r] <= lo[r + 1] and hi[r] <= hi[r + 1] for r in range(L - 1))
 
 
 def test_tile_counts_for_the_benchmark_schedules():
