@@ -36,9 +36,9 @@ def kernel_models(n_heads: int, L: int, D: int, A: int):
     pair_flops = 2 * D * A * n_heads             # one contraction over all unmasked pairs
     return {
         "hmar_fwd_kernel": {"bytes": rows * (4 * row + 4), "flops": 2 * pair_flops},
-        "hmar_delta_kernel": {"bytes": rows * (2 * row + 12), "flops": 0},
         "hmar_dkdv_kernel": {"bytes": rows * (6 * row + 8), "flops": 4 * pair_flops},
-        "hmar_dq_kernel": {"bytes": rows * (5 * row + 8), "flops": 3 * pair_flops},
+        # dQ also reads O and LSE and writes the two per-row statistics of the backward
+        "hmar_dq_kernel": {"bytes": rows * (6 * row + 12), "flops": 3 * pair_flops},
     }
 
 

@@ -97,10 +97,10 @@ hmar_status hmar_schedule_tiles(const int32_t* side_lens, int32_t num_scales, in
  * App. B.4-style timing): between hmar_profile_begin() and hmar_profile_end() every kernel
  * the library launches is bracketed by a pair of HIP events recorded on the launch stream.
  * hmar_profile_end() waits for those events and adds up, per kernel, the elapsed
- * milliseconds and the number of launches.  Kernel ids: 0 forward, 1 Delta, 2 dK/dV, 3 dQ.
+ * milliseconds and the number of launches.  Kernel ids: 0 forward, 1 dK/dV, 2 dQ.
  * total_ms_out and launches_out are HOST arrays of HMAR_NUM_KERNELS entries (either may be
  * null).  Not thread-safe against concurrent launches; adds two event records per kernel. */
-#define HMAR_NUM_KERNELS 4
+#define HMAR_NUM_KERNELS 3
 hmar_status hmar_profile_begin(void);
 hmar_status hmar_profile_end(double* total_ms_out, int64_t* launches_out);
 

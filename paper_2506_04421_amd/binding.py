@@ -170,7 +170,7 @@ def hmar_attn_bwd(Q, K, V, O, dO, LSE, side_lens, sm_scale: float = 0.0,
     return dQ, dK, dV
 
 
-KERNEL_NAMES = ("hmar_fwd_kernel", "hmar_delta_kernel", "hmar_dkdv_kernel", "hmar_dq_kernel")
+KERNEL_NAMES = ("hmar_fwd_kernel", "hmar_dkdv_kernel", "hmar_dq_kernel")
 
 
 def hmar_profile_begin() -> None:
@@ -179,10 +179,10 @@ def hmar_profile_begin() -> None:
 
 def hmar_profile_end():
     """{kernel name: (total ms, launches)} of the launches since hmar_profile_begin()."""
-    ms = (ctypes.c_double * 4)()
-    n = (ctypes.c_int64 * 4)()
+    ms = (ctypes.c_double * len(KERNEL_NAMES))()
+    n = (ctypes.c_int64 * len(KERNEL_NAMES))()
     _check(load_library().hmar_profile_end(ms, n), "hmar_profile_end")
-    return {KERNEL_NAMES[i]: (float(ms[i]), int(n[i])) for i in range(4)}
+    return {KERNEL_NAMES[i]: (float(ms[i]), int(n[i])) for i in range(len(KERNEL_NAMES))}
 
 
 def hmar_calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:

@@ -144,8 +144,8 @@ hmar_status hmar_profile_begin(void) {
 hmar_status hmar_profile_end(double* total_ms_out, int64_t* launches_out) {
     std::lock_guard<std::mutex> lock(g_prof_mu);
     g_prof_on = false;
-    double ms[HMAR_NUM_KERNELS] = {0, 0, 0, 0};
-    int64_t n[HMAR_NUM_KERNELS] = {0, 0, 0, 0};
+    double ms[HMAR_NUM_KERNELS] = {0, 0, 0};
+    int64_t n[HMAR_NUM_KERNELS] = {0, 0, 0};
     hmar_status st = HMAR_OK;
     for (auto& r : g_prof_records) {
         float t = 0.f;

@@ -1,7 +1,8 @@
 // Backward kernels of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
 //
-//   hmar_delta_kernel : Delta_i = sum_d dO_id O_id and -LSE_i * log2(e)   (one pass over O, dO)
-//   hmar_dq_kernel    : query-stationary, same walk as the forward.  Recomputes
+//   hmar_dq_kernel    : query-stationary, same walk as the forward.  First forms, for its own
+//                       rows, -Delta_i = -sum_d dO_id O_id and -LSE_i * log2(e) and leaves them
+//                       in the workspace for the dK/dV kernel (launched after it).  Recomputes
 //                       P^T = exp(S^T - LSE), dP^T = V dO^T, dS^T = P^T o (dP^T - Delta) and
 //                       accumulates dQ^T += K^T dS^T.
 //   hmar_dkdv_kernel  : key-stationary, walks the transposed schedule (a key of scale k is
@@ -19,8 +20,9 @@ namespace hmar {
 
 struct BwdParams {
     const __bf16* Q; const __bf16* K; const __bf16* V; const __bf16* dO;
-    const float* neg_lse2;   // -LSE * log2(e), from the Delta kernel
-    const float* delta;
+    const __bf16* O; const float* LSE;
+    float* neg_lse2;         // -LSE * log2(e): written by the dQ kernel, read by the dK/dV kernel
+    float* neg_delta;        // -Delta: likewise
     __bf16* dQ; __bf16* dK; __bf16* dV;
     const Item* items; const int32_t* row_lo; const int32_t* row_hi;
     int n_items, n_heads, L;
@@ -31,31 +33,9 @@ struct BwdParams {
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
-__global__ __launch_bounds__(256) void hmar_delta_kernel(const __bf16* __restrict__ O, const __bf16* __restrict__ dO,
-                                                         const float* __restrict__ LSE, float* __restrict__ delta,
-                                                         float* __restrict__ neg_lse2, long long n_rows) {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    const long long row = idx >> 3;
-    const int c = (int)(idx & 7);
-    float acc = 0.f;
-    if (row < n_rows) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(O + row * kD + c * 8);
-        const u32x4 b = *reinterpret_cast<const u32x4*>(dO + row * kD + c * 8);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc += bf16_lo(a[i]) * bf16_lo(b[i]) + bf16_hi(a[i]) * bf16_hi(b[i]);
-    }
-    acc += __shfl_xor(acc, 1);
-    acc += __shfl_xor(acc, 2);
-    acc += __shfl_xor(acc, 4);
-    if (row < n_rows && c == 0) {
-        delta[row] = acc;
-        neg_lse2[row] = -LSE[row] * kLog2e;
-    }
-}
-
 // ------------------------------------------------------------------------------------- dQ
 #ifndef HMAR_DQ_MIN_WAVES
-#define HMAR_DQ_MIN_WAVES 2
+#define HMAR_DQ_MIN_WAVES 4
 #endif
 __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(BwdParams p) {
     // ring of kStages stages, each a K tile followed by a V tile
@@ -86,7 +66,6 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;
-    const bool row_valid = wq0 + lr < it.own_end;
     const int qrow = min(wq0 + lr, it.own_end - 1);
     const int lo = p.row_lo[qrow], hi = p.row_hi[qrow];
     // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
@@ -100,8 +79,24 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         q[t] = *reinterpret_cast<const bf16x8*>(p.Q + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
         dob[t] = *reinterpret_cast<const bf16x8*>(p.dO + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
     }
-    const float nl2 = p.neg_lse2[(size_t)head * p.L + qrow];
-    const float delta = p.delta[(size_t)head * p.L + qrow];
+    // -Delta of this lane's row: each half-wave holds 32 of the row's 64 dO values
+    const float nl2 = -p.LSE[(size_t)head * p.L + qrow] * kLog2e;
+    float ndelta;
+    {
+        float acc = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const u32x4 ov = *reinterpret_cast<const u32x4*>(p.O + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
+            const u32x4 gv = __builtin_bit_cast(u32x4, dob[t]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc += bf16_lo(ov[i]) * bf16_lo(gv[i]) + bf16_hi(ov[i]) * bf16_hi(gv[i]);
+        }
+        ndelta = -half_sum(acc);
+    }
+    if (wq0 + lr < it.own_end && h == 0) {
+        p.neg_lse2[(size_t)head * p.L + qrow] = nl2;
+        p.neg_delta[(size_t)head * p.L + qrow] = ndelta;
+    }
 
     f32x16 dq[2];
 #pragma unroll
@@ -112,7 +107,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
     // make the compiler wait for these registers here, not inside the loop (see the forward);
     // loads complete in order, so tiles 0 and 1 have landed as well
     asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]), "v"(dob[0]), "v"(dob[1]), "v"(dob[2]),
-                 "v"(dob[3]), "v"(nl2), "v"(delta));
+                 "v"(dob[3]), "v"(nl2), "v"(ndelta));
     HMAR_WAIT_DMA_AND_BARRIER(0);
 
     int st = 0;
@@ -127,6 +122,8 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
             const int lim_lo = lo - kt - 4 * h, lim_hi = hi - kt - 4 * h;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
+                // (no explicit operand staging here: at 4 wavefronts per SIMD the extra
+                // registers cost more in occupancy than the batched LDS reads gain)
                 f32x16 s, dp;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
@@ -139,7 +136,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, nl2));
-                    s[i] = pv * (dp[i] - delta);
+                    s[i] = pv * (dp[i] + ndelta);
                 }
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub) {
@@ -157,25 +154,18 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         st = st + 1 == kStages ? 0 : st + 1;
     }
 
-    if (wave_active && row_valid) {
-        __bf16* orow = p.dQ + head_off + (size_t)(wq0 + lr) * kD;
-        const float sc = p.sm_scale;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                store4_bf16(orow + 32 * mb + 8 * j + 4 * h, dq[mb][4 * j] * sc, dq[mb][4 * j + 1] * sc,
-                            dq[mb][4 * j + 2] * sc, dq[mb][4 * j + 3] * sc);
-    }
+    if (wave_active)
+        store_block_rows(smem_base + wave * kPatchBytes, dq, p.sm_scale, p.dQ + head_off + (size_t)wq0 * kD,
+                         it.own_end - wq0, lane);
 }
 
 // ---------------------------------------------------------------------------------- dK, dV
 // Register budget: 3 wavefronts per SIMD (168 VGPRs) hides more latency than 2 with a
 // roomier allocation; measured on the 256px training shape.
 #ifndef HMAR_DKDV_MIN_WAVES
-#define HMAR_DKDV_MIN_WAVES 3
+#define HMAR_DKDV_MIN_WAVES 2
 #endif
-__global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kernel(BwdParams p) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_DKDV_MIN_WAVES, HMAR_DKDV_MIN_WAVES))) void hmar_dkdv_kernel(BwdParams p) {
     // ring of kStages stages, each a Q tile followed by a dO tile; then the per-row statistics
     __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
     __shared__ __attribute__((aligned(256))) float nl2_s[kStages][kTile];
@@ -190,7 +180,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
     const __bf16* Qh = p.Q + head_off;
     const __bf16* Gh = p.dO + head_off;
     const float* NLh = p.neg_lse2 + (size_t)head * p.L;
-    const float* Dh = p.delta + (size_t)head * p.L;
+    const float* Dh = p.neg_delta + (size_t)head * p.L;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
     const uint32_t smem_base = lds_address(smem);
     const uint32_t nl2_base = lds_address(nl2_s), delta_base = lds_address(delta_s);
@@ -213,7 +203,6 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
 
     const int wk0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wk0 < it.own_end;
-    const bool row_valid = wk0 + lr < it.own_end;
     const int krow = min(wk0 + lr, it.own_end - 1);
     const int lo = p.row_lo[krow], hi = p.row_hi[krow];       // queries that see this key
     // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
@@ -252,39 +241,65 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
             const int lim_lo = lo - qt - 4 * h, lim_hi = hi - qt - 4 * h;
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
+                // Operands are fetched from LDS in batches ahead of the contractions that use
+                // them (the scheduling barriers keep the compiler from sinking each read next to
+                // its use, which would expose the LDS latency once per matrix instruction).
                 f32x16 s, dp;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+                bf16x8 aq[4], ag[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    s = mfma32(lds_a_row(Qt, lo_, qb, t), kreg[t], s);
-                    dp = mfma32(lds_a_row(Gt, lo_, qb, t), vreg[t], dp);
+                    aq[t] = lds_a_row(Qt, lo_, qb, t);
+                    ag[t] = lds_a_row(Gt, lo_, qb, t);
                 }
-                mask_block(s, 32 * qb, lim_lo, lim_hi, need_lo, need_hi);
+                // statistics of the block's query rows 32qb + 8j + 4h + r (register 4j + r):
+                // -Delta seeds the dP accumulator, so dP - Delta costs no vector instruction
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    // statistics of query rows 32qb + 8j + 4h .. +3 of the tile
-                    const f32x4 l4 = *(lds_f32x4*)(nl2_t + (32 * qb + 8 * j) * 4);
                     const f32x4 d4 = *(lds_f32x4*)(delta_t + (32 * qb + 8 * j) * 4);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) { s[4 * j + r] = 0.f; dp[4 * j + r] = d4[r]; }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    s = mfma32(aq[t], kreg[t], s);
+                    dp = mfma32(ag[t], vreg[t], dp);
+                }
+                // transposed operands of the second pair of contractions and the row statistics,
+                // requested before the exponentials so that their latency hides behind them
+                bf16x8 tg[2][2], tq[2][2];
+                f32x4 l4[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) l4[j] = *(lds_f32x4*)(nl2_t + (32 * qb + 8 * j) * 4);
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) {
+                        tg[sub][mb] = lds_a_tr(Gt, lo_, mb, 2 * qb + sub);
+                        tq[sub][mb] = lds_a_tr(Qt, lo_, mb, 2 * qb + sub);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+                mask_block(s, 32 * qb, lim_lo, lim_hi, need_lo, need_hi);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int i = 4 * j + r;
-                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, l4[r]));
+                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, l4[j][r]));
                         s[i] = pv;
-                        dp[i] = pv * (dp[i] - d4[r]);
+                        dp[i] = pv * dp[i];
                     }
-                }
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub) {
-                    const int e0 = 8 * sub, tp = 2 * qb + sub;
+                    const int e0 = 8 * sub;
                     const bf16x8 pb = pack8(s[e0 + 0], s[e0 + 1], s[e0 + 2], s[e0 + 3],
                                             s[e0 + 4], s[e0 + 5], s[e0 + 6], s[e0 + 7]);
                     const bf16x8 dsb = pack8(dp[e0 + 0], dp[e0 + 1], dp[e0 + 2], dp[e0 + 3],
                                              dp[e0 + 4], dp[e0 + 5], dp[e0 + 6], dp[e0 + 7]);
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb) {
-                        dv[mb] = mfma32(lds_a_tr(Gt, lo_, mb, tp), pb, dv[mb]);
-                        dk[mb] = mfma32(lds_a_tr(Qt, lo_, mb, tp), dsb, dk[mb]);
+                        dv[mb] = mfma32(tg[sub][mb], pb, dv[mb]);
+                        dk[mb] = mfma32(tq[sub][mb], dsb, dk[mb]);
                     }
                 }
             }
@@ -297,19 +312,10 @@ __global__ __launch_bounds__(kThreads, HMAR_DKDV_MIN_WAVES) void hmar_dkdv_kerne
         st = st + 1 == kStages ? 0 : st + 1;
     }
 
-    if (wave_active && row_valid) {
-        __bf16* krow_out = p.dK + head_off + (size_t)(wk0 + lr) * kD;
-        __bf16* vrow_out = p.dV + head_off + (size_t)(wk0 + lr) * kD;
-        const float sc = p.sm_scale;
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int d0 = 32 * mb + 8 * j + 4 * h;
-                store4_bf16(krow_out + d0, dk[mb][4 * j] * sc, dk[mb][4 * j + 1] * sc,
-                            dk[mb][4 * j + 2] * sc, dk[mb][4 * j + 3] * sc);
-                store4_bf16(vrow_out + d0, dv[mb][4 * j], dv[mb][4 * j + 1], dv[mb][4 * j + 2], dv[mb][4 * j + 3]);
-            }
+    if (wave_active) {
+        const uint32_t patch = smem_base + wave * kPatchBytes;
+        store_block_rows(patch, dk, p.sm_scale, p.dK + head_off + (size_t)wk0 * kD, it.own_end - wk0, lane);
+        store_block_rows(patch, dv, 1.0f, p.dV + head_off + (size_t)wk0 * kD, it.own_end - wk0, lane);
     }
 }
 
@@ -334,24 +340,15 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
                       const float* LSE, void* dQ, void* dK, void* dV, float* workspace,
                       const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream) {
     const long long n_rows = (long long)n_heads * s.L;
-    const long long dgroups = (n_rows * 8 + 255) / 256;
-    if (dgroups <= 0 || dgroups > 0x7fffffffLL) return hipErrorInvalidValue;
-    float* delta = workspace;
-    float* neg_lse2 = workspace + n_rows;
-    profile_before(kKernelDelta, stream);
-    hipLaunchKernelGGL(hmar_delta_kernel, dim3((unsigned)dgroups), dim3(256), 0, stream,
-                       static_cast<const __bf16*>(O), static_cast<const __bf16*>(dO), LSE, delta, neg_lse2, n_rows);
-    hipError_t e = hipGetLastError();
-    profile_after(kKernelDelta, stream);
-    if (e != hipSuccess) return e;
-
     BwdParams p;
     p.Q = static_cast<const __bf16*>(Q);
     p.K = static_cast<const __bf16*>(K);
     p.V = static_cast<const __bf16*>(V);
     p.dO = static_cast<const __bf16*>(dO);
-    p.neg_lse2 = neg_lse2;
-    p.delta = delta;
+    p.O = static_cast<const __bf16*>(O);
+    p.LSE = LSE;
+    p.neg_delta = workspace;
+    p.neg_lse2 = workspace + n_rows;
     p.dQ = static_cast<__bf16*>(dQ);
     p.dK = static_cast<__bf16*>(dK);
     p.dV = static_cast<__bf16*>(dV);
@@ -360,7 +357,8 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
     p.c = sm_scale * kLog2e;
     p.sm_scale = sm_scale;
 
-    for (int dir = 1; dir >= 0; --dir) {
+    // dQ first: it also produces the per-row statistics the dK/dV kernel streams
+    for (int dir = 0; dir < 2; ++dir) {
         p.items = static_cast<const Item*>(s.items[dir]);
         p.row_lo = s.row_lo[dir];
         p.row_hi = s.row_hi[dir];
@@ -371,7 +369,7 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
         profile_before(kid, stream);
         if (dir == 1) hipLaunchKernelGGL(hmar_dkdv_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
         else          hipLaunchKernelGGL(hmar_dq_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
-        e = hipGetLastError();
+        const hipError_t e = hipGetLastError();
         profile_after(kid, stream);
         if (e != hipSuccess) return e;
     }

@@ -253,4 +253,35 @@ __device__ __forceinline__ void store4_bf16(__bf16* dst, float a, float b, float
     *reinterpret_cast<u32x2*>(dst) = u;
 }
 
+// Write a wavefront's result block to global memory as bf16 rows.  The block is the pair of
+// fp32 accumulators acc[0], acc[1] in the C layout (lane = result row lr, registers =
+// columns 32*mb + 8*(i/4) + 4h + i%4).  Storing it directly would scatter 8-byte pieces over
+// 32 rows per instruction; instead it is transposed through a private LDS patch
+// (32 rows x kPatchPitch bytes) and leaves as full 128-byte rows, 8 rows per instruction.
+// `patch` is the LDS address of this wavefront's patch, `out` points at the wavefront's
+// first row, rows >= nrows are not written.  LDS operations of one wavefront execute in
+// order, so no barrier is needed between the writes and the reads.
+constexpr int kPatchPitch = 144;                     // 128 + 16: keeps 16-byte alignment
+constexpr int kPatchBytes = 32 * kPatchPitch;        // per wavefront
+__device__ __forceinline__ void store_block_rows(uint32_t patch, const f32x16 (&acc)[2], float scale,
+                                                 __bf16* out, int nrows, int lane) {
+    typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+    typedef const __attribute__((address_space(3))) u32x4 lds_u32x4;
+    const int lr = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32x2 v = {pack_bf16(acc[mb][4 * j] * scale, acc[mb][4 * j + 1] * scale),
+                             pack_bf16(acc[mb][4 * j + 2] * scale, acc[mb][4 * j + 3] * scale)};
+            *(lds_u32x2*)(patch + lr * kPatchPitch + (32 * mb + 8 * j + 4 * h) * 2) = v;
+        }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 8 * i + (lane >> 3), chunk = lane & 7;
+        const u32x4 v = *(lds_u32x4*)(patch + row * kPatchPitch + chunk * 16);
+        if (row < nrows) *reinterpret_cast<u32x4*>(out + (size_t)row * kD + chunk * 8) = v;
+    }
+}
+
 }  // namespace hmar

@@ -28,7 +28,7 @@ struct FwdParams {
 constexpr float kRescaleThreshold = 8.0f;
 
 #ifndef HMAR_FWD_MIN_WAVES
-#define HMAR_FWD_MIN_WAVES 2
+#define HMAR_FWD_MIN_WAVES 4
 #endif
 __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(FwdParams p) {
     // ring of kStages stages, each a K tile followed by a V tile
@@ -151,19 +151,13 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
         st = st + 1 == kStages ? 0 : st + 1;
     }
 
+    // every wavefront has passed the last barrier: the ring is free and serves as the patch
+    // through which the output block is turned into full rows
     if (wave_active) {
         const float l = half_sum(lsum);
-        const float inv = 1.0f / l;
-        if (row_valid) {
-            __bf16* orow = p.O + head_off + (size_t)(wq0 + lr) * kD;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    store4_bf16(orow + 32 * mb + 8 * j + 4 * h, o[mb][4 * j] * inv, o[mb][4 * j + 1] * inv,
-                                o[mb][4 * j + 2] * inv, o[mb][4 * j + 3] * inv);
-            if (h == 0) p.LSE[(size_t)head * p.L + wq0 + lr] = (m_ref + log2f(l)) * kLn2;
-        }
+        store_block_rows(smem_base + wave * kPatchBytes, o, 1.0f / l, p.O + head_off + (size_t)wq0 * kD,
+                         it.own_end - wq0, lane);
+        if (row_valid && h == 0) p.LSE[(size_t)head * p.L + wq0 + lr] = (m_ref + log2f(l)) * kLn2;
     }
 }
 

@@ -15,7 +15,7 @@ struct DeviceSchedule {
 };
 
 // Per-kernel event bracketing for hmar_profile_begin/end (no-ops unless profiling is on).
-enum KernelId { kKernelFwd = 0, kKernelDelta = 1, kKernelDkDv = 2, kKernelDq = 3, kNumKernels = 4 };
+enum KernelId { kKernelFwd = 0, kKernelDkDv = 1, kKernelDq = 2, kNumKernels = 3 };
 void profile_before(int kernel_id, hipStream_t stream);
 void profile_after(int kernel_id, hipStream_t stream);
 
