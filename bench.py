@@ -98,6 +98,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch the plain copy kernel (for rocprofv3 --pmc traffic calibration)")
     args = ap.parse_args()
@@ -153,14 +154,34 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    def timed_steps(run_step):
+        for i in range(args.warmup):
+            run_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            run_step(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_eager = timed_steps(step)
+    # The step is three short kernels: launched one by one from Python the host can become
+    # the limit, so the timed region replays one captured HIP graph per buffer set (same
+    # kernels, same work, launch cost off the critical path).
+    ms_per_step, launch = ms_eager, "eager launches"
+    if not args.no_graph:
+        side = torch.cuda.Stream(device=dev)
+        graphs = []
+        with torch.cuda.stream(side):
+            for s_ in sets:
+                g_ = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_, stream=side):
+                    fwd(s_)
+                    bwd(s_)
+                graphs.append(g_)
+        torch.cuda.synchronize()
+        ms_graph = timed_steps(lambda i: graphs[i % len(graphs)].replay())
+        ms_per_step, launch = ms_graph, "hipGraph replay (one graph per buffer set)"
 
     # forward and backward separately, HIP events on the launch stream
     def timed(fn):
@@ -213,7 +234,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: sides {list(w.sides)}, L={w.L}, B={w.B}, H={w.H}, D={w.D}, "
                                f"Markovian mask, fwd+bwd, iid N(0,1) bf16 seed {w.seed}",
-                   "allowed_pairs_per_head": A, "buffer_sets": len(sets)},
+                   "allowed_pairs_per_head": A, "buffer_sets": len(sets), "launch": launch},
+        "ms_per_step_eager": ms_eager,
         "pct_mfma_peak": 100.0 * value / MFMA_PEAK_TFLOPS,
         "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "fwd_tflops": flops_fwd / (fwd_ms * 1e-3) / 1e12, "bwd_tflops": flops_bwd / (bwd_ms * 1e-3) / 1e12,

@@ -67,9 +67,18 @@ def _check(code: int, what: str) -> None:
         raise HmarError(f"{what} failed: {status_string(code)}")
 
 
+_SIDES_CACHE = {}
+
+
 def _sides_array(side_lens: Sequence[int]):
-    sides = [int(s) for s in side_lens]
-    return (ctypes.c_int32 * len(sides))(*sides), len(sides)
+    """(ctypes int32 array, count, L) of a schedule; cached, the hot path calls this per launch."""
+    key = tuple(side_lens)
+    hit = _SIDES_CACHE.get(key)
+    if hit is None:
+        sides = [int(s) for s in key]
+        hit = ((ctypes.c_int32 * len(sides))(*sides), len(sides), sum(s * s for s in sides))
+        _SIDES_CACHE[key] = hit
+    return hit
 
 
 def _bf16_4d(name: str, t: torch.Tensor, shape=None):
@@ -82,6 +91,24 @@ def _bf16_4d(name: str, t: torch.Tensor, shape=None):
     return t
 
 
+class _NoSwitch:
+    def __enter__(self):
+        return None
+
+    def __exit__(self, *exc):
+        return False
+
+
+_NO_SWITCH = _NoSwitch()
+
+
+def _on_device(device):
+    """Context that makes `device` current for the call; free when it already is."""
+    if torch.cuda.current_device() == (device.index if device.index is not None else torch.cuda.current_device()):
+        return _NO_SWITCH
+    return torch.cuda.device(device)
+
+
 def _stream_handle(t: torch.Tensor) -> int:
     return torch.cuda.current_stream(t.device).cuda_stream
 
@@ -89,7 +116,7 @@ def _stream_handle(t: torch.Tensor) -> int:
 def hmar_schedule_describe(side_lens: Sequence[int]) -> Tuple[list, int]:
     """(prefix sums off[0..K], allowed (query, key) pairs per head); host only."""
     lib = load_library()
-    arr, n = _sides_array(side_lens)
+    arr, n, _ = _sides_array(side_lens)
     offs = (ctypes.c_int32 * (n + 1))()
     pairs = ctypes.c_int64(0)
     _check(lib.hmar_schedule_describe(arr, n, offs, ctypes.byref(pairs)), "hmar_schedule_describe")
@@ -99,8 +126,7 @@ def hmar_schedule_describe(side_lens: Sequence[int]) -> Tuple[list, int]:
 def hmar_schedule_tiles(side_lens: Sequence[int], which: int):
     """(items [(own_begin, own_end, other_begin, other_end)], row_lo, row_hi); host only."""
     lib = load_library()
-    arr, n = _sides_array(side_lens)
-    L = sum(int(s) * int(s) for s in side_lens)
+    arr, n, L = _sides_array(side_lens)
     cnt = ctypes.c_int32(0)
     _check(lib.hmar_schedule_tiles(arr, n, which, None, 0, ctypes.byref(cnt), None, None), "hmar_schedule_tiles")
     items = (ctypes.c_int32 * (4 * cnt.value))()
@@ -125,10 +151,10 @@ def hmar_attn_fwd(Q, K, V, side_lens, sm_scale: float = 0.0, O=None, LSE=None):
     _bf16_4d("O", O, Q.shape)
     if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, L) or not LSE.is_contiguous():
         raise HmarError("LSE must be a contiguous fp32 tensor of shape [B, H, L]")
-    arr, n = _sides_array(side_lens)
-    if sum(int(s) * int(s) for s in side_lens) != L:
+    arr, n, L_sched = _sides_array(side_lens)
+    if L_sched != L:
         raise HmarError("sequence length does not match the scale schedule")
-    with torch.cuda.device(Q.device):
+    with _on_device(Q.device):
         code = lib.hmar_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
                                  arr, n, B, H, D, float(sm_scale), _stream_handle(Q))
     _check(code, "hmar_attn_fwd")
@@ -137,7 +163,7 @@ def hmar_attn_fwd(Q, K, V, side_lens, sm_scale: float = 0.0, O=None, LSE=None):
 
 def hmar_attn_bwd_workspace_bytes(side_lens, B: int, H: int, D: int) -> int:
     lib = load_library()
-    arr, n = _sides_array(side_lens)
+    arr, n, _ = _sides_array(side_lens)
     return int(lib.hmar_attn_bwd_workspace_bytes(arr, n, B, H, D))
 
 
@@ -154,14 +180,14 @@ def hmar_attn_bwd(Q, K, V, O, dO, LSE, side_lens, sm_scale: float = 0.0,
     dQ = torch.empty_like(Q) if dQ is None else _bf16_4d("dQ", dQ, Q.shape)
     dK = torch.empty_like(Q) if dK is None else _bf16_4d("dK", dK, Q.shape)
     dV = torch.empty_like(Q) if dV is None else _bf16_4d("dV", dV, Q.shape)
-    arr, n = _sides_array(side_lens)
-    if sum(int(s) * int(s) for s in side_lens) != L:
+    arr, n, L_sched = _sides_array(side_lens)
+    if L_sched != L:
         raise HmarError("sequence length does not match the scale schedule")
-    need = int(lib.hmar_attn_bwd_workspace_bytes(arr, n, B, H, D))
     if workspace is None:
+        need = int(lib.hmar_attn_bwd_workspace_bytes(arr, n, B, H, D))
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
     ws_bytes = workspace.numel() * workspace.element_size()
-    with torch.cuda.device(Q.device):
+    with _on_device(Q.device):
         code = lib.hmar_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
                                  LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
                                  arr, n, B, H, D, float(sm_scale), workspace.data_ptr(), ws_bytes,

@@ -242,3 +242,34 @@ def test_runs_on_a_side_stream():
     heads = _all_heads(w.B, w.H)
     _compare(dict(O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV),
              _oracle_heads(Q, K, V, dO, w.sides, 0.125, heads), heads, "side-stream")
+
+
+def test_hip_graph_replays_match_eager_launches():
+    # the benchmark times captured graphs: every replay must reproduce the eager result
+    # bit for bit (the kernels are deterministic), with eager work in between
+    w = si.WORKLOADS["256px_b16_h16"]
+    Q, K, V, dO = si.draw((2, 3, w.L, w.D), seed=11, n_tensors=4)
+    d = _dev()
+    q, k, v, g = (t.to(d) for t in (Q, K, V, dO))
+    O, LSE = hm.hmar_attn_fwd(q, k, v, w.sides)
+    dQ, dK, dV = hm.hmar_attn_bwd(q, k, v, O, g, LSE, w.sides)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (O, LSE, dQ, dK, dV)]
+    ws = torch.empty(hm.hmar_attn_bwd_workspace_bytes(w.sides, 2, 3, w.D), dtype=torch.uint8, device=d)
+    out = [torch.empty_like(t) for t in ref]
+    side = torch.cuda.Stream(device=d)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            hm.hmar_attn_fwd(q, k, v, w.sides, 0.0, O=out[0], LSE=out[1])
+            hm.hmar_attn_bwd(q, k, v, out[0], g, out[1], w.sides, 0.0, dQ=out[2], dK=out[3], dV=out[4], workspace=ws)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for t in out:
+            t.zero_()                                   # eager work between the replays
+        hm.hmar_attn_fwd(k, q, v, w.sides)              # and an unrelated eager launch
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(out, ref):
+            assert torch.equal(a, b), rep
