@@ -59,8 +59,27 @@ hmar_status hmar_attn_fwd(const void* Q, const void* K, const void* V, void* O, 
                           const int32_t* side_lens, int32_t num_scales,
                           int32_t B, int32_t H, int32_t D, float sm_scale, void* stream);
 
+/* The same forward under a chosen mask.  HMAR_MASK_MARKOV is the mask above;
+ * HMAR_MASK_BLOCK_CAUSAL is VAR's block-causal mask (paper Sec. 2, App. B.2: scale k attends
+ * to every scale <= k, bidirectionally inside a scale), the pattern the paper's
+ * micro-benchmark (App. B.4) compares against.  Everything else as hmar_attn_fwd. */
+typedef enum { HMAR_MASK_MARKOV = 0, HMAR_MASK_BLOCK_CAUSAL = 1 } hmar_mask_kind;
+hmar_status hmar_attn_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                 const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
+                                 int32_t B, int32_t H, int32_t D, float sm_scale, void* stream);
+
+/* One KV-cache-free inference step (paper Sec. 3.1, last paragraph; Sec. 5.2): the n_cur
+ * tokens of the scale being generated attend to the n_prev tokens that stand for everything
+ * before it and to themselves; nothing is cached between steps.
+ * Q, O: device bf16 [B,H,n_cur,D]; K, V: device bf16 [B,H,n_prev+n_cur,D], predecessor block
+ * first; LSE: device fp32 [B,H,n_cur].  n_prev >= 0 (0 for the first scale), n_cur >= 1.
+ * Equals rows of hmar_attn_fwd restricted to one scale. */
+hmar_status hmar_attn_step_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                               int32_t n_prev, int32_t n_cur, int32_t B, int32_t H, int32_t D,
+                               float sm_scale, void* stream);
+
 /* Bytes of device workspace hmar_attn_bwd needs for this problem (0 on invalid arguments).
- * The workspace holds two fp32 [B,H,L] arrays: Delta_i = sum_d dO_id O_id and -LSE_i*log2(e). */
+ * The workspace holds two fp32 [B,H,L] arrays: -Delta_i = -sum_d dO_id O_id and -LSE_i*log2(e). */
 size_t hmar_attn_bwd_workspace_bytes(const int32_t* side_lens, int32_t num_scales,
                                      int32_t B, int32_t H, int32_t D);
 
@@ -76,6 +95,14 @@ hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const voi
                           int32_t B, int32_t H, int32_t D, float sm_scale,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same backward under a chosen mask (see hmar_attn_fwd_masked); the workspace size does
+ * not depend on the mask. */
+hmar_status hmar_attn_bwd_masked(const void* Q, const void* K, const void* V, const void* O,
+                                 const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                                 const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
+                                 int32_t B, int32_t H, int32_t D, float sm_scale,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host-only description of a schedule (no device work): prefix sums off[0..num_scales]
  * of side^2 and the number of unmasked (query, key) pairs per head.  Either output
  * pointer may be null. */
@@ -83,7 +110,8 @@ hmar_status hmar_schedule_describe(const int32_t* side_lens, int32_t num_scales,
                                    int32_t* offsets_out, int64_t* allowed_pairs_out);
 
 /* Host-only export of the tile work lists the kernels walk, for inspection and tests.
- *   which = 0: forward / dQ list (query-row ranges), 1: dK/dV list (key-row ranges).
+ *   which = 0: forward / dQ list (query-row ranges), 1: dK/dV list (key-row ranges);
+ *   add 2 for the block-causal mask instead of the Markovian one.
  * Each item is 4 int32: {own_begin, own_end, other_begin, other_end}: the rows the
  * workgroup owns and the contiguous range of the other operand's rows it visits.
  * Writes up to max_items items to items_out (may be null) and the item count to

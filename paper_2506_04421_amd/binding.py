@@ -40,6 +40,13 @@ def load_library() -> ctypes.CDLL:
     lib.hmar_status_string.argtypes = [ctypes.c_int]
     lib.hmar_attn_fwd.restype = ctypes.c_int
     lib.hmar_attn_fwd.argtypes = [vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, f32, vp]
+    lib.hmar_attn_fwd_masked.restype = ctypes.c_int
+    lib.hmar_attn_fwd_masked.argtypes = [vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, i32, f32, vp]
+    lib.hmar_attn_step_fwd.restype = ctypes.c_int
+    lib.hmar_attn_step_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp]
+    lib.hmar_attn_bwd_masked.restype = ctypes.c_int
+    lib.hmar_attn_bwd_masked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, i32, f32,
+                                         vp, sz, vp]
     lib.hmar_attn_bwd_workspace_bytes.restype = sz
     lib.hmar_attn_bwd_workspace_bytes.argtypes = [pi32, i32, i32, i32, i32]
     lib.hmar_attn_bwd.restype = ctypes.c_int
@@ -137,8 +144,17 @@ def hmar_schedule_tiles(side_lens: Sequence[int], which: int):
     return [tuple(flat[4 * i:4 * i + 4]) for i in range(cnt.value)], list(lo), list(hi)
 
 
+HMAR_MASK_MARKOV = 0
+HMAR_MASK_BLOCK_CAUSAL = 1
+
+
 def hmar_attn_fwd(Q, K, V, side_lens, sm_scale: float = 0.0, O=None, LSE=None):
     """Forward on the tensors' device and current stream.  Returns (O bf16, LSE fp32)."""
+    return hmar_attn_fwd_masked(Q, K, V, side_lens, HMAR_MASK_MARKOV, sm_scale, O, LSE)
+
+
+def hmar_attn_fwd_masked(Q, K, V, side_lens, mask_kind: int, sm_scale: float = 0.0, O=None, LSE=None):
+    """Forward under the Markovian (0) or block-causal (1) mask.  Returns (O bf16, LSE fp32)."""
     lib = load_library()
     _bf16_4d("Q", Q)
     B, H, L, D = Q.shape
@@ -155,9 +171,30 @@ def hmar_attn_fwd(Q, K, V, side_lens, sm_scale: float = 0.0, O=None, LSE=None):
     if L_sched != L:
         raise HmarError("sequence length does not match the scale schedule")
     with _on_device(Q.device):
-        code = lib.hmar_attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
-                                 arr, n, B, H, D, float(sm_scale), _stream_handle(Q))
-    _check(code, "hmar_attn_fwd")
+        code = lib.hmar_attn_fwd_masked(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                                        arr, n, int(mask_kind), B, H, D, float(sm_scale), _stream_handle(Q))
+    _check(code, "hmar_attn_fwd_masked")
+    return O, LSE
+
+
+def hmar_attn_step_fwd(Q, K, V, n_prev: int, sm_scale: float = 0.0, O=None, LSE=None):
+    """One inference step: Q [B,H,n_cur,D] against K, V [B,H,n_prev+n_cur,D].  Returns (O, LSE)."""
+    lib = load_library()
+    _bf16_4d("Q", Q)
+    B, H, n_cur, D = Q.shape
+    _bf16_4d("K", K, (B, H, int(n_prev) + n_cur, D))
+    _bf16_4d("V", V, K.shape)
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, H, n_cur), dtype=torch.float32, device=Q.device)
+    _bf16_4d("O", O, Q.shape)
+    if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, n_cur) or not LSE.is_contiguous():
+        raise HmarError("LSE must be a contiguous fp32 tensor of shape [B, H, n_cur]")
+    with _on_device(Q.device):
+        code = lib.hmar_attn_step_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                                      int(n_prev), n_cur, B, H, D, float(sm_scale), _stream_handle(Q))
+    _check(code, "hmar_attn_step_fwd")
     return O, LSE
 
 
@@ -170,6 +207,12 @@ def hmar_attn_bwd_workspace_bytes(side_lens, B: int, H: int, D: int) -> int:
 def hmar_attn_bwd(Q, K, V, O, dO, LSE, side_lens, sm_scale: float = 0.0,
                   dQ=None, dK=None, dV=None, workspace=None):
     """Backward on the tensors' device and current stream.  Returns (dQ, dK, dV) bf16."""
+    return hmar_attn_bwd_masked(Q, K, V, O, dO, LSE, side_lens, HMAR_MASK_MARKOV, sm_scale, dQ, dK, dV, workspace)
+
+
+def hmar_attn_bwd_masked(Q, K, V, O, dO, LSE, side_lens, mask_kind: int, sm_scale: float = 0.0,
+                         dQ=None, dK=None, dV=None, workspace=None):
+    """Backward under the Markovian (0) or block-causal (1) mask.  Returns (dQ, dK, dV) bf16."""
     lib = load_library()
     _bf16_4d("Q", Q)
     B, H, L, D = Q.shape
@@ -188,11 +231,11 @@ def hmar_attn_bwd(Q, K, V, O, dO, LSE, side_lens, sm_scale: float = 0.0,
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
     ws_bytes = workspace.numel() * workspace.element_size()
     with _on_device(Q.device):
-        code = lib.hmar_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
-                                 LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                                 arr, n, B, H, D, float(sm_scale), workspace.data_ptr(), ws_bytes,
-                                 _stream_handle(Q))
-    _check(code, "hmar_attn_bwd")
+        code = lib.hmar_attn_bwd_masked(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+                                        LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                        arr, n, int(mask_kind), B, H, D, float(sm_scale), workspace.data_ptr(),
+                                        ws_bytes, _stream_handle(Q))
+    _check(code, "hmar_attn_bwd_masked")
     return dQ, dK, dV
 
 

@@ -9,6 +9,7 @@
 #include <map>
 #include <memory>
 #include <mutex>
+#include <tuple>
 #include <utility>
 #include <vector>
 
@@ -26,19 +27,21 @@ struct CachedSchedule {
 };
 
 std::mutex g_mu;
-std::map<std::pair<int, std::vector<int32_t>>, std::unique_ptr<CachedSchedule>> g_cache;
+// key: device, mask kind, sides (for an inference step: {n_prev, n_cur})
+std::map<std::tuple<int, int32_t, std::vector<int32_t>>, std::unique_ptr<CachedSchedule>> g_cache;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Checks that need no device.  On success *L is the sequence length.
-hmar_status check_problem(const int32_t* side_lens, int32_t num_scales, int32_t B, int32_t H, int32_t D,
-                          hmar::Schedule* sched) {
+hmar_status check_problem(const int32_t* side_lens, int32_t num_scales, int32_t mask_kind, int32_t B, int32_t H,
+                          int32_t D, hmar::Schedule* sched) {
     if (!side_lens || num_scales < 1 || B < 1 || H < 1 || D < 1) return HMAR_ERR_INVALID_ARG;
+    if (mask_kind != HMAR_MASK_MARKOV && mask_kind != HMAR_MASK_BLOCK_CAUSAL) return HMAR_ERR_INVALID_ARG;
     for (int32_t k = 0; k < num_scales && k < HMAR_MAX_SCALES; ++k)
         if (side_lens[k] < 1) return HMAR_ERR_INVALID_ARG;
     if (num_scales > HMAR_MAX_SCALES) return HMAR_ERR_UNSUPPORTED;
     if (D != 64) return HMAR_ERR_UNSUPPORTED;
-    if (!hmar::build_schedule(side_lens, num_scales, kRowsPerItem, HMAR_MAX_SCALES, HMAR_MAX_SEQ_LEN, sched))
+    if (!hmar::build_schedule(side_lens, num_scales, mask_kind, kRowsPerItem, HMAR_MAX_SCALES, HMAR_MAX_SEQ_LEN, sched))
         return HMAR_ERR_UNSUPPORTED;   // only L > HMAR_MAX_SEQ_LEN (or side > 46340) is left
     if ((int64_t)B * H > (1 << 24)) return HMAR_ERR_UNSUPPORTED;
     return HMAR_OK;
@@ -50,7 +53,7 @@ hmar_status get_device_schedule(hmar::Schedule&& host, hipStream_t stream, const
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return HMAR_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mu);
-    auto key = std::make_pair(dev, host.sides);
+    auto key = std::make_tuple(dev, host.mask_kind, host.sides);
     auto it = g_cache.find(key);
     if (it != g_cache.end()) { *out = &it->second->dev; return HMAR_OK; }
 
@@ -61,6 +64,10 @@ hmar_status get_device_schedule(hmar::Schedule&& host, hipStream_t stream, const
     // layout: items[0] | items[1] | row_lo[0] | row_hi[0] | row_lo[1] | row_hi[1]
     const size_t item_bytes[2] = {s.items[0].size() * sizeof(hmar::TileItem), s.items[1].size() * sizeof(hmar::TileItem)};
     const size_t total = item_bytes[0] + item_bytes[1] + 4 * L * sizeof(int32_t);
+    for (int d = 0; d < 2; ++d) {      // an inference-step schedule has no backward direction
+        cs->host.row_lo[d].resize(L, 0);
+        cs->host.row_hi[d].resize(L, 0);
+    }
     std::vector<unsigned char> staging(total);
     size_t o = 0;
     size_t off_items[2], off_lo[2], off_hi[2];
@@ -85,6 +92,7 @@ hmar_status get_device_schedule(hmar::Schedule&& host, hipStream_t stream, const
         cs->dev.row_hi[d] = reinterpret_cast<const int32_t*>(base + off_hi[d]);
     }
     cs->dev.L = s.L;
+    cs->dev.Lk = s.Lk;
     *out = &cs->dev;
     g_cache.emplace(std::move(key), std::move(cs));
     return HMAR_OK;
@@ -174,14 +182,14 @@ const char* hmar_status_string(hmar_status s) {
     return "HMAR_ERR_UNKNOWN";
 }
 
-hmar_status hmar_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
-                          const int32_t* side_lens, int32_t num_scales,
-                          int32_t B, int32_t H, int32_t D, float sm_scale, void* stream) {
+hmar_status hmar_attn_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                 const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
+                                 int32_t B, int32_t H, int32_t D, float sm_scale, void* stream) {
     if (!Q || !K || !V || !O || !LSE) return HMAR_ERR_INVALID_ARG;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return HMAR_ERR_INVALID_ARG;
     if (!std::isfinite(sm_scale)) return HMAR_ERR_INVALID_ARG;
     hmar::Schedule host;
-    hmar_status st = check_problem(side_lens, num_scales, B, H, D, &host);
+    hmar_status st = check_problem(side_lens, num_scales, mask_kind, B, H, D, &host);
     if (st != HMAR_OK) return st;
     const hmar::DeviceSchedule* ds = nullptr;
     st = get_device_schedule(std::move(host), static_cast<hipStream_t>(stream), &ds);
@@ -191,25 +199,48 @@ hmar_status hmar_attn_fwd(const void* Q, const void* K, const void* V, void* O, 
     return e == hipSuccess ? HMAR_OK : HMAR_ERR_HIP;
 }
 
+hmar_status hmar_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                          const int32_t* side_lens, int32_t num_scales,
+                          int32_t B, int32_t H, int32_t D, float sm_scale, void* stream) {
+    return hmar_attn_fwd_masked(Q, K, V, O, LSE, side_lens, num_scales, HMAR_MASK_MARKOV, B, H, D, sm_scale, stream);
+}
+
+hmar_status hmar_attn_step_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                               int32_t n_prev, int32_t n_cur, int32_t B, int32_t H, int32_t D,
+                               float sm_scale, void* stream) {
+    if (!Q || !K || !V || !O || !LSE) return HMAR_ERR_INVALID_ARG;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE)) return HMAR_ERR_INVALID_ARG;
+    if (!std::isfinite(sm_scale) || n_prev < 0 || n_cur < 1 || B < 1 || H < 1 || D < 1) return HMAR_ERR_INVALID_ARG;
+    if (D != 64 || (int64_t)B * H > (1 << 24)) return HMAR_ERR_UNSUPPORTED;
+    hmar::Schedule host;
+    if (!hmar::build_step_schedule(n_prev, n_cur, kRowsPerItem, HMAR_MAX_SEQ_LEN, &host)) return HMAR_ERR_UNSUPPORTED;
+    const hmar::DeviceSchedule* ds = nullptr;
+    hmar_status st = get_device_schedule(std::move(host), static_cast<hipStream_t>(stream), &ds);
+    if (st != HMAR_OK) return st;
+    hipError_t e = hmar::launch_fwd(Q, K, V, O, LSE, *ds, B * H, resolve_scale(sm_scale, D),
+                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HMAR_OK : HMAR_ERR_HIP;
+}
+
 size_t hmar_attn_bwd_workspace_bytes(const int32_t* side_lens, int32_t num_scales,
                                      int32_t B, int32_t H, int32_t D) {
     hmar::Schedule host;
-    if (check_problem(side_lens, num_scales, B, H, D, &host) != HMAR_OK) return 0;
+    if (check_problem(side_lens, num_scales, HMAR_MASK_MARKOV, B, H, D, &host) != HMAR_OK) return 0;
     return 2 * (size_t)B * H * host.L * sizeof(float);
 }
 
-hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
-                          const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
-                          const int32_t* side_lens, int32_t num_scales,
-                          int32_t B, int32_t H, int32_t D, float sm_scale,
-                          void* workspace, size_t workspace_bytes, void* stream) {
+hmar_status hmar_attn_bwd_masked(const void* Q, const void* K, const void* V, const void* O,
+                                 const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                                 const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
+                                 int32_t B, int32_t H, int32_t D, float sm_scale,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
     if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return HMAR_ERR_INVALID_ARG;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(dO) || !aligned16(LSE) ||
         !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
         return HMAR_ERR_INVALID_ARG;
     if (!std::isfinite(sm_scale)) return HMAR_ERR_INVALID_ARG;
     hmar::Schedule host;
-    hmar_status st = check_problem(side_lens, num_scales, B, H, D, &host);
+    hmar_status st = check_problem(side_lens, num_scales, mask_kind, B, H, D, &host);
     if (st != HMAR_OK) return st;
     const size_t need = 2 * (size_t)B * H * host.L * sizeof(float);
     if (!workspace || workspace_bytes < need) return HMAR_ERR_WORKSPACE;
@@ -222,6 +253,15 @@ hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const voi
     return e == hipSuccess ? HMAR_OK : HMAR_ERR_HIP;
 }
 
+hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
+                          const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                          const int32_t* side_lens, int32_t num_scales,
+                          int32_t B, int32_t H, int32_t D, float sm_scale,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+    return hmar_attn_bwd_masked(Q, K, V, O, dO, LSE, dQ, dK, dV, side_lens, num_scales, HMAR_MASK_MARKOV, B, H, D,
+                                sm_scale, workspace, workspace_bytes, stream);
+}
+
 hmar_status hmar_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
     if (!dst || !src || (bytes & 15u) || !aligned16(dst) || !aligned16(src)) return HMAR_ERR_INVALID_ARG;
     return hmar::launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? HMAR_OK : HMAR_ERR_HIP;
@@ -230,7 +270,7 @@ hmar_status hmar_calibration_copy(void* dst, const void* src, size_t bytes, void
 hmar_status hmar_schedule_describe(const int32_t* side_lens, int32_t num_scales,
                                    int32_t* offsets_out, int64_t* allowed_pairs_out) {
     hmar::Schedule host;
-    hmar_status st = check_problem(side_lens, num_scales, 1, 1, 64, &host);
+    hmar_status st = check_problem(side_lens, num_scales, HMAR_MASK_MARKOV, 1, 1, 64, &host);
     if (st != HMAR_OK) return st;
     if (offsets_out) std::memcpy(offsets_out, host.off.data(), host.off.size() * sizeof(int32_t));
     if (allowed_pairs_out) *allowed_pairs_out = host.allowed_pairs;
@@ -240,9 +280,12 @@ hmar_status hmar_schedule_describe(const int32_t* side_lens, int32_t num_scales,
 hmar_status hmar_schedule_tiles(const int32_t* side_lens, int32_t num_scales, int32_t which,
                                 int32_t* items_out, int32_t max_items, int32_t* n_items_out,
                                 int32_t* row_lo_out, int32_t* row_hi_out) {
-    if (which < 0 || which > 1 || !n_items_out || max_items < 0) return HMAR_ERR_INVALID_ARG;
+    // which: bit 0 = direction, bit 1 = block-causal mask instead of the Markovian one
+    if (which < 0 || which > 3 || !n_items_out || max_items < 0) return HMAR_ERR_INVALID_ARG;
+    const int32_t mask_kind = (which & 2) ? HMAR_MASK_BLOCK_CAUSAL : HMAR_MASK_MARKOV;
+    which &= 1;
     hmar::Schedule host;
-    hmar_status st = check_problem(side_lens, num_scales, 1, 1, 64, &host);
+    hmar_status st = check_problem(side_lens, num_scales, mask_kind, 1, 1, 64, &host);
     if (st != HMAR_OK) return st;
     const auto& items = host.items[which];
     *n_items_out = (int32_t)items.size();

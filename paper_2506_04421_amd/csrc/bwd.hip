@@ -162,14 +162,20 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 // ---------------------------------------------------------------------------------- dK, dV
 // Register budget: 3 wavefronts per SIMD (168 VGPRs) hides more latency than 2 with a
 // roomier allocation; measured on the 256px training shape.
+// Its register footprint, not LDS, limits this kernel to two workgroups per CU, so it can
+// afford a deeper ring than the other kernels.
+#ifndef HMAR_DKDV_STAGES
+#define HMAR_DKDV_STAGES 2
+#endif
+constexpr int kDkdvStages = HMAR_DKDV_STAGES, kDkdvAhead = kDkdvStages - 1;
 #ifndef HMAR_DKDV_MIN_WAVES
 #define HMAR_DKDV_MIN_WAVES 2
 #endif
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_DKDV_MIN_WAVES, HMAR_DKDV_MIN_WAVES))) void hmar_dkdv_kernel(BwdParams p) {
-    // ring of kStages stages, each a Q tile followed by a dO tile; then the per-row statistics
-    __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
-    __shared__ __attribute__((aligned(256))) float nl2_s[kStages][kTile];
-    __shared__ __attribute__((aligned(256))) float delta_s[kStages][kTile];
+    // ring of kDkdvStages stages, each a Q tile followed by a dO tile; then the per-row statistics
+    __shared__ __attribute__((aligned(1024))) char smem[kDkdvStages * 2 * kTileBytes];
+    __shared__ __attribute__((aligned(256))) float nl2_s[kDkdvStages][kTile];
+    __shared__ __attribute__((aligned(256))) float delta_s[kDkdvStages][kTile];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -198,7 +204,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
         else if (wave == 1) dma_floats(Dh, qt, qmax, delta_base + st * (kTile * 4), lane);
     };
 #pragma unroll
-    for (int d = 0; d < kAhead; ++d)
+    for (int d = 0; d < kDkdvAhead; ++d)
         if (d < ntiles) issue(d, d);
 
     const int wk0 = it.own_begin + wave * kRowsPerWave;
@@ -230,8 +236,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     int st = 0;
     for (int ti = 0; ti < ntiles; ++ti) {
         const int qt = q_begin + ti * kTile;
-        const bool ahead = ti + kAhead < ntiles;
-        if (ahead) issue(ti + kAhead, st >= 1 ? st - 1 : kStages - 1);
+        const bool ahead = ti + kDkdvAhead < ntiles;
+        if (ahead) issue(ti + kDkdvAhead, st >= 1 ? st - 1 : kDkdvStages - 1);
         if (wave_active && qt < whi && qt + kTile > wlo) {
             const uint32_t Qt = smem_base + st * (2 * kTileBytes);
             const uint32_t Gt = Qt + kTileBytes;
@@ -304,12 +310,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
                 }
             }
         }
-        if (ahead && kAhead > 1) {
-            if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5 * (kAhead - 1)); } else { HMAR_WAIT_DMA_AND_BARRIER(4 * (kAhead - 1)); }
+        if (ahead && kDkdvAhead > 1) {
+            if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5 * (kDkdvAhead - 1)); } else { HMAR_WAIT_DMA_AND_BARRIER(4 * (kDkdvAhead - 1)); }
         } else {
             HMAR_WAIT_DMA_AND_BARRIER(0);
         }
-        st = st + 1 == kStages ? 0 : st + 1;
+        st = st + 1 == kDkdvStages ? 0 : st + 1;
     }
 
     if (wave_active) {

@@ -17,7 +17,8 @@ struct FwdParams {
     const __bf16* Q; const __bf16* K; const __bf16* V;
     __bf16* O; float* LSE;
     const Item* items; const int32_t* row_lo; const int32_t* row_hi;
-    int n_items, n_heads, L;
+    int n_items, n_heads;
+    int L, Lk;   // rows per head of Q/O/LSE and of K/V (they differ only for an inference step)
     float c;   // sm_scale * log2(e): scores are exponentiated in base 2
 };
 
@@ -41,8 +42,8 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
     const __bf16* Qh = p.Q + head_off;
-    const __bf16* Kh = p.K + head_off;
-    const __bf16* Vh = p.V + head_off;
+    const __bf16* Kh = p.K + (size_t)head * p.Lk * kD;
+    const __bf16* Vh = p.V + (size_t)head * p.Lk * kD;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
     const uint32_t smem_base = lds_address(smem);
 
@@ -175,6 +176,7 @@ hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, floa
     p.n_items = s.n_items[0];
     p.n_heads = n_heads;
     p.L = s.L;
+    p.Lk = s.Lk;
     p.c = sm_scale * kLog2e;
     const long long groups = 8LL * ((n_heads + 7) / 8) * s.n_items[0];
     if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;

@@ -11,7 +11,8 @@ struct DeviceSchedule {
     int32_t n_items[2];
     const int32_t* row_lo[2];  // L entries
     const int32_t* row_hi[2];
-    int32_t L;
+    int32_t L;                 // rows of Q, O, LSE per head
+    int32_t Lk;                // rows of K, V per head
 };
 
 // Per-kernel event bracketing for hmar_profile_begin/end (no-ops unless profiling is on).

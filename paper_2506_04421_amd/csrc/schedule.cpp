@@ -34,10 +34,12 @@ static void partition_rows(const Schedule& s, int32_t rows_per_item, std::vector
     flush();
 }
 
-bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t rows_per_item,
+bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t mask_kind, int32_t rows_per_item,
                     int32_t max_scales, int64_t max_len, Schedule* out) {
     if (!sides || num_scales < 1 || num_scales > max_scales || rows_per_item < 32 || rows_per_item % 32) return false;
+    if (mask_kind != kMaskMarkov && mask_kind != kMaskBlockCausal) return false;
     Schedule s;
+    s.mask_kind = mask_kind;
     s.sides.assign(sides, sides + num_scales);
     s.off.assign(1, 0);
     int64_t L = 0;
@@ -47,12 +49,13 @@ bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t rows_per_i
         if (L > max_len) return false;
         s.off.push_back((int32_t)L);
     }
-    s.L = (int32_t)L;
+    s.L = s.Lk = (int32_t)L;
     const int K = num_scales;
+    const bool causal = mask_kind == kMaskBlockCausal;
     s.allowed_pairs = 0;
     for (int k = 0; k < K; ++k) {
         const int64_t n = s.off[k + 1] - s.off[k];
-        const int64_t np = k > 0 ? s.off[k] - s.off[k - 1] : 0;
+        const int64_t np = causal ? s.off[k] : (k > 0 ? s.off[k] - s.off[k - 1] : 0);
         s.allowed_pairs += n * (np + n);
     }
     for (int dir = 0; dir < 2; ++dir) {
@@ -60,8 +63,8 @@ bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t rows_per_i
         s.row_hi[dir].resize(s.L);
         for (int k = 0; k < K; ++k) {
             int32_t lo, hi;
-            if (dir == 0) { lo = s.off[std::max(k - 1, 0)]; hi = s.off[k + 1]; }
-            else          { lo = s.off[k];                  hi = s.off[std::min(k + 2, K)]; }
+            if (dir == 0) { lo = causal ? 0 : s.off[std::max(k - 1, 0)]; hi = s.off[k + 1]; }
+            else          { lo = s.off[k]; hi = causal ? s.L : s.off[std::min(k + 2, K)]; }
             for (int32_t r = s.off[k]; r < s.off[k + 1]; ++r) { s.row_lo[dir][r] = lo; s.row_hi[dir][r] = hi; }
         }
         partition_rows(s, rows_per_item, &s.items[dir]);
@@ -81,6 +84,27 @@ bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t rows_per_i
             return ca > cb;
         });
     }
+    *out = std::move(s);
+    return true;
+}
+
+bool build_step_schedule(int32_t n_prev, int32_t n_cur, int32_t rows_per_item, int64_t max_len, Schedule* out) {
+    if (n_prev < 0 || n_cur < 1 || rows_per_item < 32 || rows_per_item % 32) return false;
+    if ((int64_t)n_prev + n_cur > max_len) return false;
+    Schedule s;
+    s.mask_kind = kMaskStep;
+    s.sides = {n_prev, n_cur};
+    s.off = {0, n_cur};
+    s.L = n_cur;
+    s.Lk = n_prev + n_cur;
+    s.allowed_pairs = (int64_t)n_cur * s.Lk;
+    s.row_lo[0].assign(n_cur, 0);
+    s.row_hi[0].assign(n_cur, s.Lk);
+    // equal chunks, each a multiple of 32 rows except the last
+    const int32_t chunks = (n_cur + rows_per_item - 1) / rows_per_item;
+    int32_t per = (n_cur + chunks - 1) / chunks;
+    per = (per + 31) / 32 * 32;
+    for (int32_t b = 0; b < n_cur; b += per) s.items[0].push_back({b, std::min(b + per, n_cur), 0, s.Lk});
     *out = std::move(s);
     return true;
 }

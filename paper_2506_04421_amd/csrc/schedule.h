@@ -5,9 +5,13 @@
 // the stationary operand and visits one contiguous range of rows of the streamed
 // operand; score tiles outside that range are never loaded.
 //   direction 0 (forward, dQ): owned rows are queries, visited rows are keys.
-//       query i of scale k (0-based) pairs with keys [off[max(k-1,0)], off[k+1])
+//       Markovian mask:    query i of scale k (0-based) pairs with keys [off[max(k-1,0)], off[k+1])
+//       block-causal mask: (VAR, paper Sec. 2) with keys [0, off[k+1])
 //   direction 1 (dK/dV): owned rows are keys, visited rows are queries.
-//       key j of scale k pairs with queries [off[k], off[min(k+2,K)])
+//       Markovian mask:    key j of scale k pairs with queries [off[k], off[min(k+2,K)])
+//       block-causal mask: with queries [off[k], L)
+// A third kind describes one KV-cache-free inference step (paper Sec. 3.1, last paragraph):
+// the n_cur queries of the current scale against all n_prev + n_cur keys of the step.
 #pragma once
 #include <cstdint>
 #include <vector>
@@ -19,10 +23,14 @@ struct TileItem {
     int32_t other_begin, other_end;  // union of the owned rows' pair ranges
 };
 
+enum MaskKind : int32_t { kMaskMarkov = 0, kMaskBlockCausal = 1, kMaskStep = 2 };
+
 struct Schedule {
-    std::vector<int32_t> sides;
+    std::vector<int32_t> sides;      // for kMaskStep: {n_prev, n_cur} (token counts, not sides)
+    int32_t mask_kind = kMaskMarkov;
     std::vector<int32_t> off;        // K+1 prefix sums of side^2
-    int32_t L = 0;
+    int32_t L = 0;                   // rows of Q, O, LSE per head
+    int32_t Lk = 0;                  // rows of K, V per head (= L except for kMaskStep)
     int64_t allowed_pairs = 0;       // sum_k n_k (n_{k-1} + n_k)
     // per direction
     std::vector<TileItem> items[2];
@@ -31,7 +39,11 @@ struct Schedule {
 
 // rows_per_item: most rows one workgroup owns (a multiple of 32).  Returns false when
 // the sides are invalid (non-positive, too many, or L beyond max_len).
-bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t rows_per_item,
+bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t mask_kind, int32_t rows_per_item,
                     int32_t max_scales, int64_t max_len, Schedule* out);
+
+// One inference step: n_cur query rows, each pairing with all n_prev + n_cur key rows.
+// Only direction 0 is filled.
+bool build_step_schedule(int32_t n_prev, int32_t n_cur, int32_t rows_per_item, int64_t max_len, Schedule* out);
 
 }  // namespace hmar

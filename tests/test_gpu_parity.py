@@ -273,3 +273,66 @@ def test_hip_graph_replays_match_eager_launches():
         torch.cuda.synchronize()
         for a, b in zip(out, ref):
             assert torch.equal(a, b), rep
+
+
+@pytest.mark.parametrize("sides", [si.SIDES_TINY, (2, 5), (3, 1, 4, 1, 5), (6, 7, 8, 9, 10), si.SIDES_256])
+def test_block_causal_mask_variant(sides):
+    # VAR's block-causal mask (Sec. 2) through the same kernels; oracle = dense attention
+    # under the explicit block-causal mask and its analytic backward
+    L = sum(s * s for s in sides)
+    B, H, D = 1, 3, 64
+    Q, K, V, dO = si.draw((B, H, L, D), seed=200 + L, n_tensors=4)
+    d = _dev()
+    q, k, v, g = (t.to(d) for t in (Q, K, V, dO))
+    O, LSE = hm.hmar_attn_fwd_masked(q, k, v, sides, hm.HMAR_MASK_BLOCK_CAUSAL)
+    dQ, dK, dV = hm.hmar_attn_bwd_masked(q, k, v, O, g, LSE, sides, hm.HMAR_MASK_BLOCK_CAUSAL)
+    torch.cuda.synchronize()
+    mask = orc.block_causal_mask(sides)
+    ref = {n: [] for n in ("O", "LSE", "dQ", "dK", "dV")}
+    for hh in range(H):
+        q64, k64, v64, g64 = (si.to_f64(t[0, hh]) for t in (Q, K, V, dO))
+        o, lse, _ = orc.attn_fwd_masked(q64, k64, v64, mask, 0.125)
+        a, b, c = orc.attn_bwd_masked(q64, k64, v64, g64, mask, 0.125)
+        for n, x in zip(("O", "LSE", "dQ", "dK", "dV"), (o, lse, a, b, c)):
+            ref[n].append(x)
+    ref = {n: np.stack(x) for n, x in ref.items()}
+    heads = [(0, hh) for hh in range(H)]
+    _compare(dict(O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV), ref, heads, f"block-causal {sides}")
+    # and it differs from the Markovian result wherever a scale has a grand-predecessor
+    if len(sides) > 2:
+        Om, _ = hm.hmar_attn_fwd(q, k, v, sides)
+        assert not torch.equal(Om, O)
+
+
+@pytest.mark.parametrize("n_prev,n_cur", [(0, 1), (1, 4), (25, 36), (100, 169), (169, 256), (7, 130), (300, 33)])
+def test_inference_step_forward(n_prev, n_cur):
+    # one KV-cache-free step (Sec. 3.1): n_cur queries against the predecessor block + themselves
+    B, H, D = 2, 3, 64
+    Q = si.draw((B, H, n_cur, D), seed=300 + n_cur, n_tensors=1)[0]
+    K, V = si.draw((B, H, n_prev + n_cur, D), seed=400 + n_prev, n_tensors=2)
+    d = _dev()
+    O, LSE = hm.hmar_attn_step_fwd(Q.to(d), K.to(d), V.to(d), n_prev)
+    torch.cuda.synchronize()
+    rO, rLSE = orc.attn_step_fwd(si.to_f64(Q), si.to_f64(K), si.to_f64(V), n_prev)
+    assert np.abs(si.to_f64(O) - rO).max() <= TOL_ABS
+    assert (np.abs(si.to_f64(LSE) - rLSE) <= TOL_LSE_REL * np.maximum(1.0, np.abs(rLSE))).all()
+
+
+def test_inference_steps_reproduce_the_training_forward():
+    # all 10 steps of the 256px schedule, each fed the slices the training layout holds,
+    # give the rows of the full Markovian forward (same kernels, same tiles => bit equal
+    # is not required, the oracle bar is)
+    w = si.WORKLOADS["256px_b16_h16"]
+    Q, K, V, _ = si.draw((1, 4, w.L, w.D), seed=12, n_tensors=4)
+    d = _dev()
+    q, k, v = (t.to(d) for t in (Q, K, V))
+    O, LSE = hm.hmar_attn_fwd(q, k, v, w.sides)
+    offs = orc.scale_offsets(w.sides)
+    for s in range(len(w.sides)):
+        q0, q1 = offs[s], offs[s + 1]
+        k0 = offs[s - 1] if s > 0 else q0
+        Os, LSEs = hm.hmar_attn_step_fwd(q[:, :, q0:q1].contiguous(), k[:, :, k0:q1].contiguous(),
+                                         v[:, :, k0:q1].contiguous(), q0 - k0)
+        torch.cuda.synchronize()
+        assert (Os.float() - O[:, :, q0:q1].float()).abs().max().item() <= 1e-2
+        assert (LSEs - LSE[:, :, q0:q1]).abs().max().item() <= 1e-4

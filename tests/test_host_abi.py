@@ -143,3 +143,37 @@ def test_binding_refuses_cpu_tensors_and_wrong_dtypes():
     with pytest.raises(hm.HmarError):
         hm.hmar_attn_fwd(x, x, x, (1, 2))
     assert os.path.exists(binding.LIB_PATH)
+
+
+@pytest.mark.parametrize("sides", [si.SIDES_TINY, si.SIDES_256, (2, 5), (3, 1, 4, 1, 5), (20, 3, 20)])
+@pytest.mark.parametrize("direction", [0, 1])
+def test_block_causal_tile_schedule_covers_exactly_the_var_mask(sides, direction):
+    # `which` + 2 selects VAR's block-causal mask (Sec. 2): scale k sees every scale <= k
+    mask = orc.block_causal_mask(sides)
+    if direction == 1:
+        mask = mask.T
+    L = mask.shape[0]
+    items, lo, hi = hm.hmar_schedule_tiles(sides, direction + 2)
+    rebuilt = np.zeros_like(mask)
+    for r in range(L):
+        rebuilt[r, lo[r]:hi[r]] = True
+    assert np.array_equal(rebuilt, mask)
+    owned = np.zeros(L, dtype=int)
+    for (b, e, ob, oe) in items:
+        assert e - b <= 128 and ob == min(lo[b:e]) and oe == max(hi[b:e])
+        owned[b:e] += 1
+    assert (owned == 1).all()
+    assert all(lo[r] <= lo[r + 1] and hi[r] <= hi[r + 1] for r in range(L - 1))
+
+
+def test_step_and_masked_entry_points_reject_bad_arguments():
+    lib = hm.load_library()
+    arr = (ctypes.c_int32 * 2)(1, 2)
+    p = [0x1000 * (i + 1) for i in range(5)]
+    assert lib.hmar_attn_fwd_masked(*p, arr, 2, 7, 1, 1, 64, 0.0, None) == 1        # unknown mask kind
+    assert lib.hmar_attn_fwd_masked(*p, arr, 2, -1, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_step_fwd(*p, -1, 4, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_step_fwd(*p, 4, 0, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_step_fwd(*p, 4, 9, 1, 1, 32, 0.0, None) == 2
+    assert lib.hmar_attn_step_fwd(None, *p[1:], 4, 9, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_step_fwd(*p, 1 << 20, 9, 1, 1, 64, 0.0, None) == 2           # beyond HMAR_MAX_SEQ_LEN
