@@ -92,12 +92,80 @@ def cpu_baseline(w, A: int, budget_s: float = 15.0):
             "seconds_per_head": dt / heads}
 
 
+def other_workloads(hm, si, torch, dev, reps: int = 20):
+    """Context figures for the other shapes and entry points (GPU time from HIP events on the
+    launch stream, eager launches, one buffer set): not the headline, not part of `value`."""
+    def gpu_ms(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    res = {}
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+
+    def rnd(shape):
+        return torch.randn(shape, device=dev, generator=g).to(torch.bfloat16)
+
+    for name, mask in (("256px_b16_h16", 0), ("256px_b32_h30", 0), ("512px_b8_h24", 0), ("256px_b32_h24", 1)):
+        w = si.WORKLOADS[name]
+        shape = (w.B, w.H, w.L, w.D)
+        q, k, v, do = rnd(shape), rnd(shape), rnd(shape), rnd(shape)
+        O, LSE = hm.hmar_attn_fwd_masked(q, k, v, w.sides, mask)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        ws = torch.empty(hm.hmar_attn_bwd_workspace_bytes(w.sides, w.B, w.H, w.D), dtype=torch.uint8, device=dev)
+        f_ms = gpu_ms(lambda: hm.hmar_attn_fwd_masked(q, k, v, w.sides, mask, 0.0, O, LSE))
+        b_ms = gpu_ms(lambda: hm.hmar_attn_bwd_masked(q, k, v, O, do, LSE, w.sides, mask, 0.0, dq, dk, dv, ws))
+        n = [s * s for s in w.sides]
+        if mask == 0:
+            A = sum(n[i] * (n[i] + (n[i - 1] if i else 0)) for i in range(len(n)))
+        else:
+            A = sum(n[i] * sum(n[:i + 1]) for i in range(len(n)))
+        flops = 2 * w.D * A * w.B * w.H
+        res[name + ("_block_causal" if mask else "")] = {
+            "fwd_ms": f_ms, "bwd_ms": b_ms, "fwd_tflops": 2 * flops / f_ms / 1e9, "bwd_tflops": 5 * flops / b_ms / 1e9,
+            "fwd_bwd_tflops": 7 * flops / (f_ms + b_ms) / 1e9}
+        del q, k, v, do, O, LSE, dq, dk, dv, ws
+    # KV-cache-free inference: the 10 steps of the 256px schedule, B = 64, H = 24, forward only
+    w = si.WORKLOADS["256px_b32_h24"]
+    B, H, D = 64, 24, 64
+    n = [s * s for s in w.sides]
+    steps = []
+    for i, n_cur in enumerate(n):
+        n_prev = n[i - 1] if i else 0
+        q = rnd((B, H, n_cur, D))
+        k, v = rnd((B, H, n_prev + n_cur, D)), rnd((B, H, n_prev + n_cur, D))
+        O = torch.empty_like(q)
+        LSE = torch.empty((B, H, n_cur), dtype=torch.float32, device=dev)
+        steps.append((q, k, v, n_prev, O, LSE))
+
+    def sweep():
+        for (q, k, v, n_prev, O, LSE) in steps:
+            hm.hmar_attn_step_fwd(q, k, v, n_prev, 0.0, O, LSE)
+    ms = gpu_ms(sweep)
+    pairs = sum(n[i] * (n[i] + (n[i - 1] if i else 0)) for i in range(len(n)))
+    flops = 4 * D * pairs * B * H
+    nbytes = B * H * sum((2 * n[i] + 2 * (n[i] + (n[i - 1] if i else 0))) * D * 2 + 4 * n[i] for i in range(len(n)))
+    last = gpu_ms(lambda: hm.hmar_attn_step_fwd(*steps[-1][:4], 0.0, steps[-1][4], steps[-1][5]))
+    res["inference_steps_256px_b64_h24"] = {
+        "all_10_steps_ms": ms, "tflops": flops / ms / 1e9, "hbm_gbs": nbytes / ms / 1e6,
+        "last_step_ms": last, "last_step_tflops": 4 * D * n[-1] * (n[-1] + n[-2]) * B * H / last / 1e9}
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads (context only)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch the plain copy kernel (for rocprofv3 --pmc traffic calibration)")
@@ -243,6 +311,8 @@ def main() -> int:
         "kernel_ms": kern_ms,
         "roofline": roof,
     }
+    if not args.no_extras:
+        out["other_workloads"] = other_workloads(hm, si, torch, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, A)
     print(json.dumps(out))
