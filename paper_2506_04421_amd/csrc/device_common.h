@@ -128,6 +128,7 @@ struct LaneOffsets {
     int trB0, trB1;               // the same, 8 rows further down
     int dma_src;                  // byte offset, inside its 128-byte global row, of the 16 bytes
                                   // this lane moves (row = lane/8 of the 8 rows a wavefront writes)
+    int dma_voff;                 // byte offset of those 16 bytes from the first row of a full tile
 };
 
 __device__ __forceinline__ LaneOffsets make_lane_offsets(int lane, int wave) {
@@ -149,44 +150,51 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int lane, int wave) {
     // (4*blk + p/16) mod 8, i.e. on the parity of blk = parity of wave: one offset serves both j.
     const int r = 8 * wave + (lane >> 3);
     o.dma_src = ((lane & 7) ^ swz(r)) << 4;
+    o.dma_voff = r * kRowBytes + o.dma_src;
     return o;
 }
 
-// One global->LDS DMA load: every lane moves BYTES (16 or 4) from its own global address to
-// LDS address lds_base + lane * BYTES; lds_base must be uniform over the wavefront (it goes
-// through M0).  Written as inline assembly so that the compiler does not serialise the LDS
-// reads of the tile being computed behind the loads that run ahead into other tiles;
-// completion is awaited explicitly (wait_dma_and_barrier) before any wavefront reads the tile.
-__device__ __forceinline__ void dma16(const void* src, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(src), "s"(lds_base) : "m0", "memory");
+// One global->LDS DMA load: every lane moves 16 (or 4) bytes from global address
+// sbase + voff (sbase uniform over the wavefront, voff a per-lane byte offset) to LDS address
+// lds_base + lane * 16 (or 4); lds_base must be uniform too (it goes through M0).  Written
+// as inline assembly so that the compiler does not serialise the LDS reads of the tile being
+// computed behind the loads that run ahead into other tiles; completion is awaited
+// explicitly (wait_dma_and_barrier) before any wavefront reads the tile.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_base) : "m0", "memory");
 }
-__device__ __forceinline__ void dma4(const void* src, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-                 :: "v"(src), "s"(lds_base) : "m0", "memory");
+__device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_base) : "m0", "memory");
 }
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
 }
 
 // Issue the DMA loads of one 64-row tile: rows row0 .. row0+63 of a [rows][64] bf16 matrix
-// (clamped to row_max, so the tail re-reads a valid row), into the tile at LDS address
-// `tile` (wave-uniform).  Two loads per lane.
+// (clamped to row_max, so a ragged tail re-reads a valid row), into the tile at LDS address
+// `tile` (wave-uniform).  Two loads per lane: tile rows 8*wave + lane/8 and 32 further down.
+// For a full tile the per-lane offset is a constant of the kernel and only the scalar base
+// moves from tile to tile.
 __device__ __forceinline__ void dma_tile(const __bf16* base, int row0, int row_max, uint32_t tile,
                                          const LaneOffsets& o, int lane, int wave) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int blk = wave + 4 * j;
-        const int r = min(row0 + 8 * blk + (lane >> 3), row_max);
-        const char* src = reinterpret_cast<const char*>(base) + (size_t)r * kRowBytes + o.dma_src;
-        dma16(src, __builtin_amdgcn_readfirstlane(tile + blk * 1024));
+    const char* sbase = reinterpret_cast<const char*>(base) + (size_t)row0 * kRowBytes;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(tile + wave * 1024);
+    if (row0 + kTile - 1 <= row_max) {
+        dma16(sbase, o.dma_voff, lds0);
+        dma16(sbase + 32 * kRowBytes, o.dma_voff, lds0 + 4096);
+    } else {
+        const int r = 8 * wave + (lane >> 3), last = row_max - row0;
+        dma16(sbase, min(r, last) * kRowBytes + o.dma_src, lds0);
+        dma16(sbase, min(r + 32, last) * kRowBytes + o.dma_src, lds0 + 4096);
     }
 }
 
 // 64 consecutive fp32 (index clamped to i_max) to LDS address `dst` (wave-uniform): one
 // 4-byte DMA load per lane
 __device__ __forceinline__ void dma_floats(const float* base, int i0, int i_max, uint32_t dst, int lane) {
-    dma4(base + min(i0 + lane, i_max), __builtin_amdgcn_readfirstlane(dst));
+    dma4(base + i0, min(lane, i_max - i0) * 4, __builtin_amdgcn_readfirstlane(dst));
 }
 
 // Wait until at most N (<= 15) of this wavefront's DMA loads are outstanding and all its LDS

@@ -82,6 +82,7 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
     float m_ref = kNegBig, lsum = 0.f;
+    bool o_empty = true;              // nothing accumulated yet: the first rescale has nothing to scale
 
     // The compiler does not see the DMA loads; without this use it would wait for the Q
     // registers inside the loop, where its count would also drain the loads running ahead.
@@ -119,14 +120,17 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
             mt = half_max(mt) * p.c;
             if (__builtin_amdgcn_ballot_w64(mt > m_ref + kRescaleThreshold) != 0) {
                 const float m_new = fmaxf(m_ref, mt);
-                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-                lsum *= alpha;
+                if (!o_empty) {
+                    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                    lsum *= alpha;
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+                    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
+                        for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
+                }
                 m_ref = m_new;
             }
+            o_empty = false;
             const float neg_m = -m_ref;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
