@@ -13,6 +13,8 @@
 // workgroups: results are deterministic and nothing needs zero-initialising.  Streamed
 // tiles are row-major in LDS and serve both as row-wise operands (S, dP) and, through the
 // LDS transpose load, as transposed operands (dQ, dK, dV).
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -38,8 +40,8 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u 
 #define HMAR_DQ_MIN_WAVES 4
 #endif
 __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(BwdParams p) {
-    // ring of kStages stages, each a K tile followed by a V tile
-    __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
+    // ring of 2 stages, each a K tile followed by a V tile
+    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -60,9 +62,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         dma_tile(Kh, k_begin + ti * kTile, kmax, stage, lo_, lane, wave);
         dma_tile(Vh, k_begin + ti * kTile, kmax, stage + kTileBytes, lo_, lane, wave);
     };
-#pragma unroll
-    for (int d = 0; d < kAhead; ++d)
-        if (d < ntiles) issue(d, d);
+    issue(0, 0);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;
@@ -105,18 +105,19 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         for (int i = 0; i < 16; ++i) dq[mb][i] = 0.f;
 
     // make the compiler wait for these registers here, not inside the loop (see the forward);
-    // loads complete in order, so tiles 0 and 1 have landed as well
+    // loads complete in order, so tile 0 has landed as well
     asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]), "v"(dob[0]), "v"(dob[1]), "v"(dob[2]),
                  "v"(dob[3]), "v"(nl2), "v"(ndelta));
     HMAR_WAIT_DMA_AND_BARRIER(0);
 
-    int st = 0;
-    for (int ti = 0; ti < ntiles; ++ti) {
+    // one tile: request the next one, compute, wait for the request; the stage is a template
+    // constant so that every LDS address of the step is a per-lane register plus an immediate
+    auto tile_step = [&](const int ti, auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
         const int kt = k_begin + ti * kTile;
-        const bool ahead = ti + kAhead < ntiles;
-        if (ahead) issue(ti + kAhead, st >= 1 ? st - 1 : kStages - 1);
+        if (ti + 1 < ntiles) issue(ti + 1, ST ^ 1);
         if (wave_active && kt < whi && kt + kTile > wlo) {
-            const uint32_t Kt = smem_base + st * (2 * kTileBytes);
+            const uint32_t Kt = smem_base + ST * (2 * kTileBytes);
             const uint32_t Vt = Kt + kTileBytes;
             const bool need_lo = kt < full_lo, need_hi = kt + kTile > full_hi;
             const int lim_lo = lo - kt - 4 * h, lim_hi = hi - kt - 4 * h;
@@ -149,9 +150,12 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
                 }
             }
         }
-        if (ahead && kAhead > 1) { HMAR_WAIT_DMA_AND_BARRIER(4 * (kAhead - 1)); }
-        else                     { HMAR_WAIT_DMA_AND_BARRIER(0); }
-        st = st + 1 == kStages ? 0 : st + 1;
+        HMAR_WAIT_DMA_AND_BARRIER(0);     // the tile requested above has landed and this one is free
+    };
+    for (int ti = 0; ti < ntiles; ti += 2) {
+        tile_step(ti, std::integral_constant<int, 0>{});
+        if (ti + 1 >= ntiles) break;
+        tile_step(ti + 1, std::integral_constant<int, 1>{});
     }
 
     if (wave_active)
@@ -164,18 +168,14 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 // roomier allocation; measured on the 256px training shape.
 // Its register footprint, not LDS, limits this kernel to two workgroups per CU, so it can
 // afford a deeper ring than the other kernels.
-#ifndef HMAR_DKDV_STAGES
-#define HMAR_DKDV_STAGES 2
-#endif
-constexpr int kDkdvStages = HMAR_DKDV_STAGES, kDkdvAhead = kDkdvStages - 1;
 #ifndef HMAR_DKDV_MIN_WAVES
 #define HMAR_DKDV_MIN_WAVES 2
 #endif
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_DKDV_MIN_WAVES, HMAR_DKDV_MIN_WAVES))) void hmar_dkdv_kernel(BwdParams p) {
-    // ring of kDkdvStages stages, each a Q tile followed by a dO tile; then the per-row statistics
-    __shared__ __attribute__((aligned(1024))) char smem[kDkdvStages * 2 * kTileBytes];
-    __shared__ __attribute__((aligned(256))) float nl2_s[kDkdvStages][kTile];
-    __shared__ __attribute__((aligned(256))) float delta_s[kDkdvStages][kTile];
+    // ring of 2 stages, each a Q tile followed by a dO tile; then the per-row statistics
+    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+    __shared__ __attribute__((aligned(256))) float nl2_s[2][kTile];
+    __shared__ __attribute__((aligned(256))) float delta_s[2][kTile];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -203,9 +203,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
         if (wave == 0) dma_floats(NLh, qt, qmax, nl2_base + st * (kTile * 4), lane);
         else if (wave == 1) dma_floats(Dh, qt, qmax, delta_base + st * (kTile * 4), lane);
     };
-#pragma unroll
-    for (int d = 0; d < kDkdvAhead; ++d)
-        if (d < ntiles) issue(d, d);
+    issue(0, 0);
 
     const int wk0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wk0 < it.own_end;
@@ -233,16 +231,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
                  "v"(vreg[2]), "v"(vreg[3]));
     HMAR_WAIT_DMA_AND_BARRIER(0);
 
-    int st = 0;
-    for (int ti = 0; ti < ntiles; ++ti) {
+    auto tile_step = [&](const int ti, auto stage_c) {     // see the dQ kernel
+        constexpr int ST = decltype(stage_c)::value;
         const int qt = q_begin + ti * kTile;
-        const bool ahead = ti + kDkdvAhead < ntiles;
-        if (ahead) issue(ti + kDkdvAhead, st >= 1 ? st - 1 : kDkdvStages - 1);
+        if (ti + 1 < ntiles) issue(ti + 1, ST ^ 1);
         if (wave_active && qt < whi && qt + kTile > wlo) {
-            const uint32_t Qt = smem_base + st * (2 * kTileBytes);
+            const uint32_t Qt = smem_base + ST * (2 * kTileBytes);
             const uint32_t Gt = Qt + kTileBytes;
-            const uint32_t nl2_t = nl2_base + st * (kTile * 4) + 16 * h;
-            const uint32_t delta_t = delta_base + st * (kTile * 4) + 16 * h;
+            const uint32_t nl2_t = nl2_base + ST * (kTile * 4) + 16 * h;
+            const uint32_t delta_t = delta_base + ST * (kTile * 4) + 16 * h;
             const bool need_lo = qt < full_lo, need_hi = qt + kTile > full_hi;
             const int lim_lo = lo - qt - 4 * h, lim_hi = hi - qt - 4 * h;
 #pragma unroll
@@ -310,12 +307,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
                 }
             }
         }
-        if (ahead && kDkdvAhead > 1) {
-            if (wave < 2) { HMAR_WAIT_DMA_AND_BARRIER(5 * (kDkdvAhead - 1)); } else { HMAR_WAIT_DMA_AND_BARRIER(4 * (kDkdvAhead - 1)); }
-        } else {
-            HMAR_WAIT_DMA_AND_BARRIER(0);
-        }
-        st = st + 1 == kDkdvStages ? 0 : st + 1;
+        HMAR_WAIT_DMA_AND_BARRIER(0);
+    };
+    for (int ti = 0; ti < ntiles; ti += 2) {
+        tile_step(ti, std::integral_constant<int, 0>{});
+        if (ti + 1 >= ntiles) break;
+        tile_step(ti + 1, std::integral_constant<int, 1>{});
     }
 
     if (wave_active) {

@@ -45,14 +45,11 @@ constexpr int kRowBytes = 128;    // one bf16 row of the head dimension
 constexpr int kTileBytes = kTile * kRowBytes;   // 8 KB
 constexpr int kThreads = 256;     // 4 wavefronts
 constexpr int kRowsPerWave = 32;
-// Two stages (32 KB per workgroup) measured faster than three or four on the 256px training
-// shape: the LDS saved lets a fourth workgroup live on each CU, and with 3-4 wavefronts per
-// SIMD other workgroups hide the load latency better than a deeper ring does.
-#ifndef HMAR_STAGES
-#define HMAR_STAGES 2
-#endif
-constexpr int kStages = HMAR_STAGES;   // LDS ring depth
-constexpr int kAhead = kStages - 1;    // the DMA loads run this many tiles ahead of the compute
+// Every kernel streams its tiles through a ring of two LDS stages, the DMA loads running one
+// tile ahead of the compute.  Two stages (32 KB per workgroup) measured faster than three or
+// four on the 256px training shape: the LDS saved lets a fourth workgroup live on each CU, and
+// with 3-4 wavefronts per SIMD other workgroups hide the load latency better than a deeper
+// ring does.  The kernels unroll their tile loop by two so that the stage is a constant.
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;

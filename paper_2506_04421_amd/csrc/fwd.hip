@@ -1,13 +1,15 @@
 // Forward kernel of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
 //
 // One workgroup (4 wavefronts) owns up to 128 consecutive query rows, 32 per wavefront,
-// and streams the key/value rows of their two-scale windows through a 3-deep ring of LDS
-// tiles (64 rows each) filled by global->LDS DMA loads that run two tiles ahead.
+// and streams the key/value rows of their two-scale windows through a two-stage ring of LDS
+// tiles (64 rows each) filled by global->LDS DMA loads that run one tile ahead.
 // Scores are computed transposed (S^T = K Q^T) so that a lane holds one query column:
 // the row maximum and sum are then lane-local apart from one exchange between the two
 // half-waves, and the probability tile is already laid out as the B operand of the
 // second contraction O^T += V^T P^T, whose A operand comes from the row-major V tile
 // through the LDS transpose load.
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -32,8 +34,8 @@ constexpr float kRescaleThreshold = 8.0f;
 #define HMAR_FWD_MIN_WAVES 4
 #endif
 __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(FwdParams p) {
-    // ring of kStages stages, each a K tile followed by a V tile
-    __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kTileBytes];
+    // ring of 2 stages, each a K tile followed by a V tile
+    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
@@ -50,16 +52,14 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
     const int k_begin = it.other_begin, k_end = it.other_end, kmax = k_end - 1;
     const int ntiles = (k_end - k_begin + kTile - 1) / kTile;
 
-    // 4 DMA loads per lane and tile (2 for K, 2 for V); the first two tiles are requested
-    // before anything else so that their latency overlaps the rest of the prologue
+    // 4 DMA loads per lane and tile (2 for K, 2 for V); the first tile is requested before
+    // anything else so that its latency overlaps the rest of the prologue
     auto issue = [&](int ti, int st) {
         const uint32_t stage = smem_base + st * (2 * kTileBytes);
         dma_tile(Kh, k_begin + ti * kTile, kmax, stage, lo_, lane, wave);
         dma_tile(Vh, k_begin + ti * kTile, kmax, stage + kTileBytes, lo_, lane, wave);
     };
-#pragma unroll
-    for (int d = 0; d < kAhead; ++d)
-        if (d < ntiles) issue(d, d);
+    issue(0, 0);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;               // uniform over the wavefront
@@ -87,17 +87,19 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
     // The compiler does not see the DMA loads; without this use it would wait for the Q
     // registers inside the loop, where its count would also drain the loads running ahead.
     asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]));
-    // Loads complete in order: the registers above were requested after tiles 0 and 1.
+    // Loads complete in order: the registers above were requested after tile 0.
     HMAR_WAIT_DMA_AND_BARRIER(0);
 
-    int st = 0;                       // stage of tile ti
-    for (int ti = 0; ti < ntiles; ++ti) {
+    // One tile: request the next one, compute, wait for the request.  The stage is a template
+    // constant (the loop below alternates the two instantiations) so that every LDS address of
+    // the step is a per-lane register plus an immediate offset.
+    auto tile_step = [&](const int ti, auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
         const int kt = k_begin + ti * kTile;
-        const bool ahead = ti + kAhead < ntiles;
-        // the tile kAhead ahead goes into the stage every wave left at the last barrier
-        if (ahead) issue(ti + kAhead, st >= 1 ? st - 1 : kStages - 1);
+        // the next tile goes into the other stage, which every wavefront left at the last barrier
+        if (ti + 1 < ntiles) issue(ti + 1, ST ^ 1);
         if (wave_active && kt < whi && kt + kTile > wlo) {
-            const uint32_t Kt = smem_base + st * (2 * kTileBytes);
+            const uint32_t Kt = smem_base + ST * (2 * kTileBytes);
             const uint32_t Vt = Kt + kTileBytes;
             f32x16 s[2];
 #pragma unroll
@@ -150,10 +152,12 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
                     o[mb] = mfma32(lds_a_tr(Vt, lo_, mb, tp), pb, o[mb]);
             }
         }
-        // tile ti+1 has landed; up to kAhead-1 later tiles (4 loads each) may be in flight
-        if (ahead && kAhead > 1) { HMAR_WAIT_DMA_AND_BARRIER(4 * (kAhead - 1)); }
-        else                     { HMAR_WAIT_DMA_AND_BARRIER(0); }
-        st = st + 1 == kStages ? 0 : st + 1;
+        HMAR_WAIT_DMA_AND_BARRIER(0);     // the tile requested above has landed and this one is free
+    };
+    for (int ti = 0; ti < ntiles; ti += 2) {
+        tile_step(ti, std::integral_constant<int, 0>{});
+        if (ti + 1 >= ntiles) break;
+        tile_step(ti + 1, std::integral_constant<int, 1>{});
     }
 
     // every wavefront has passed the last barrier: the ring is free and serves as the patch
