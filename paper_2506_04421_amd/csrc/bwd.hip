@@ -1,10 +1,12 @@
 // Backward kernels of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
 //
-//   hmar_dq_kernel    : query-stationary, same walk as the forward.  First forms, for its own
-//                       rows, -Delta_i = -sum_d dO_id O_id and -LSE_i * log2(e) and leaves them
-//                       in the workspace for the dK/dV kernel (launched after it).  Recomputes
-//                       P^T = exp(S^T - LSE), dP^T = V dO^T, dS^T = P^T o (dP^T - Delta) and
-//                       accumulates dQ^T += K^T dS^T.
+//   hmar_dq_kernel    : query-stationary, same walk as the forward but over the heads in reverse
+//                       order (the forward before it and the dK/dV kernel after it both walk
+//                       forwards, so each kernel begins where its predecessor ended).  First
+//                       forms, for its own rows, -Delta_i = -sum_d dO_id O_id and
+//                       -LSE_i * log2(e) and leaves them in the workspace for the dK/dV kernel
+//                       (launched after it).  Recomputes P^T = exp(S^T - LSE), dP^T = V dO^T,
+//                       dS^T = P^T o (dP^T - Delta) and accumulates dQ^T += K^T dS^T.
 //   hmar_dkdv_kernel  : key-stationary, walks the transposed schedule (a key of scale k is
 //                       seen by the queries of scales k and k+1).  Recomputes P and dS with
 //                       the keys in the lane dimension and accumulates dV^T += dO^T P,
@@ -44,7 +46,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
     __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
 
     int head, item_id;
-    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
+    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id, true)) return;
     const Item it = p.items[item_id];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;

@@ -61,12 +61,16 @@ typedef const __attribute__((address_space(1))) void global_void;
 
 // Workgroup -> (head, item).  Workgroups are handed to the 8 XCDs round-robin, so all
 // items of one head are given ids that are congruent mod 8: they then run on one XCD and
-// share its L2 for the rows they re-read.
-__device__ __forceinline__ bool map_workgroup(int n_items, int n_heads, int* head, int* item) {
+// share its L2 for the rows they re-read.  With `reverse` the heads are walked from the last
+// to the first: a kernel that follows another one over the same tensors then starts on the
+// heads that kernel touched last, which are the ones still in the last-level cache.
+__device__ __forceinline__ bool map_workgroup(int n_items, int n_heads, int* head, int* item, bool reverse = false) {
     const int wg = blockIdx.x;
     const int xcd = wg & 7;
     const int slot = wg >> 3;
-    *head = (slot / n_items) * 8 + xcd;
+    int group = slot / n_items;
+    if (reverse) group = (n_heads + 7) / 8 - 1 - group;
+    *head = group * 8 + xcd;
     *item = slot % n_items;
     return *head < n_heads;
 }
