@@ -64,6 +64,11 @@ hmar_status hmar_attn_fwd(const void* Q, const void* K, const void* V, void* O, 
  * to every scale <= k, bidirectionally inside a scale), the pattern the paper's
  * micro-benchmark (App. B.4) compares against.  Everything else as hmar_attn_fwd. */
 typedef enum { HMAR_MASK_MARKOV = 0, HMAR_MASK_BLOCK_CAUSAL = 1 } hmar_mask_kind;
+/* May be OR-ed into the mask_kind argument of the *_masked entry points: side_lens then holds
+ * the token count n_k of each scale itself instead of a side length, for token maps that are
+ * not square (the paper's scales are H_k x W_k maps, Sec. 2: n_k = H_k * W_k).  Row order
+ * inside a scale is the caller's business: attention inside a scale is bidirectional. */
+#define HMAR_SCALE_COUNTS 0x100
 hmar_status hmar_attn_fwd_masked(const void* Q, const void* K, const void* V, void* O, float* LSE,
                                  const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
                                  int32_t B, int32_t H, int32_t D, float sm_scale, void* stream);
@@ -95,8 +100,13 @@ hmar_status hmar_attn_bwd(const void* Q, const void* K, const void* V, const voi
                           int32_t B, int32_t H, int32_t D, float sm_scale,
                           void* workspace, size_t workspace_bytes, void* stream);
 
-/* The same backward under a chosen mask (see hmar_attn_fwd_masked); the workspace size does
- * not depend on the mask. */
+/* Workspace size for hmar_attn_bwd_masked with the same side_lens / mask_kind arguments (the
+ * mask does not change it, HMAR_SCALE_COUNTS does: L = sum_k n_k).  0 on invalid arguments. */
+size_t hmar_attn_bwd_workspace_bytes_masked(const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
+                                            int32_t B, int32_t H, int32_t D);
+
+/* The same backward under a chosen mask (see hmar_attn_fwd_masked); workspace of at least
+ * hmar_attn_bwd_workspace_bytes_masked(...) bytes. */
 hmar_status hmar_attn_bwd_masked(const void* Q, const void* K, const void* V, const void* O,
                                  const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
                                  const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
@@ -111,7 +121,8 @@ hmar_status hmar_schedule_describe(const int32_t* side_lens, int32_t num_scales,
 
 /* Host-only export of the tile work lists the kernels walk, for inspection and tests.
  *   which = 0: forward / dQ list (query-row ranges), 1: dK/dV list (key-row ranges);
- *   add 2 for the block-causal mask instead of the Markovian one.
+ *   add 2 for the block-causal mask instead of the Markovian one, add 4 when side_lens holds
+ *   token counts (see HMAR_SCALE_COUNTS).
  * Each item is 4 int32: {own_begin, own_end, other_begin, other_end}: the rows the
  * workgroup owns and the contiguous range of the other operand's rows it visits.
  * Writes up to max_items items to items_out (may be null) and the item count to

@@ -40,6 +40,9 @@ __all__ = [
     "token_scale_ids",
     "markov_mask",
     "block_causal_mask",
+    "scale_ids_from_counts",
+    "markov_mask_from_counts",
+    "block_causal_mask_from_counts",
     "allowed_pairs",
     "attn_fwd",
     "attn_bwd",
@@ -90,6 +93,30 @@ def markov_mask(side_lens):
 def block_causal_mask(side_lens):
     """VAR's block-causal mask (Sec. 2): scale k sees every scale <= k."""
     sid = token_scale_ids(side_lens)
+    return sid[None, :] <= sid[:, None]
+
+
+def scale_ids_from_counts(token_counts):
+    """scale id (1-based) of every token when scale k holds token_counts[k-1] = H_k * W_k tokens
+    of a token map that need not be square (Sec. 2)."""
+    counts = [int(n) for n in token_counts]
+    if len(counts) == 0 or any(n < 1 for n in counts):
+        raise ValueError("token counts must be a non-empty list of positive integers")
+    ids = []
+    for k, n in enumerate(counts, start=1):
+        ids.extend([k] * n)
+    return np.asarray(ids, dtype=np.int64)
+
+
+def markov_mask_from_counts(token_counts):
+    """The Markovian mask (Sec. 3.1, Eq. 4) for scales given by their token counts."""
+    sid = scale_ids_from_counts(token_counts)
+    return (sid[None, :] == sid[:, None]) | (sid[None, :] == sid[:, None] - 1)
+
+
+def block_causal_mask_from_counts(token_counts):
+    """VAR's block-causal mask (Sec. 2) for scales given by their token counts."""
+    sid = scale_ids_from_counts(token_counts)
     return sid[None, :] <= sid[:, None]
 
 

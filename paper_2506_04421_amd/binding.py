@@ -49,6 +49,8 @@ def load_library() -> ctypes.CDLL:
                                          vp, sz, vp]
     lib.hmar_attn_bwd_workspace_bytes.restype = sz
     lib.hmar_attn_bwd_workspace_bytes.argtypes = [pi32, i32, i32, i32, i32]
+    lib.hmar_attn_bwd_workspace_bytes_masked.restype = sz
+    lib.hmar_attn_bwd_workspace_bytes_masked.argtypes = [pi32, i32, i32, i32, i32, i32]
     lib.hmar_attn_bwd.restype = ctypes.c_int
     lib.hmar_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, f32, vp, sz, vp]
     lib.hmar_schedule_describe.restype = ctypes.c_int
@@ -77,13 +79,14 @@ def _check(code: int, what: str) -> None:
 _SIDES_CACHE = {}
 
 
-def _sides_array(side_lens: Sequence[int]):
-    """(ctypes int32 array, count, L) of a schedule; cached, the hot path calls this per launch."""
-    key = tuple(side_lens)
+def _sides_array(side_lens: Sequence[int], counts: bool = False):
+    """(ctypes int32 array, count, L) of a schedule given as side lengths (or, with `counts`, as
+    token counts per scale); cached, the hot path calls this per launch."""
+    key = (tuple(side_lens), bool(counts))
     hit = _SIDES_CACHE.get(key)
     if hit is None:
-        sides = [int(s) for s in key]
-        hit = ((ctypes.c_int32 * len(sides))(*sides), len(sides), sum(s * s for s in sides))
+        sides = [int(s) for s in key[0]]
+        hit = ((ctypes.c_int32 * len(sides))(*sides), len(sides), sum(s if counts else s * s for s in sides))
         _SIDES_CACHE[key] = hit
     return hit
 
@@ -133,7 +136,7 @@ def hmar_schedule_describe(side_lens: Sequence[int]) -> Tuple[list, int]:
 def hmar_schedule_tiles(side_lens: Sequence[int], which: int):
     """(items [(own_begin, own_end, other_begin, other_end)], row_lo, row_hi); host only."""
     lib = load_library()
-    arr, n, L = _sides_array(side_lens)
+    arr, n, L = _sides_array(side_lens, bool(which & 4))
     cnt = ctypes.c_int32(0)
     _check(lib.hmar_schedule_tiles(arr, n, which, None, 0, ctypes.byref(cnt), None, None), "hmar_schedule_tiles")
     items = (ctypes.c_int32 * (4 * cnt.value))()
@@ -146,6 +149,7 @@ def hmar_schedule_tiles(side_lens: Sequence[int], which: int):
 
 HMAR_MASK_MARKOV = 0
 HMAR_MASK_BLOCK_CAUSAL = 1
+HMAR_SCALE_COUNTS = 0x100      # OR into mask_kind: side_lens holds token counts per scale
 
 
 def hmar_attn_fwd(Q, K, V, side_lens, sm_scale: float = 0.0, O=None, LSE=None):
@@ -154,7 +158,8 @@ def hmar_attn_fwd(Q, K, V, side_lens, sm_scale: float = 0.0, O=None, LSE=None):
 
 
 def hmar_attn_fwd_masked(Q, K, V, side_lens, mask_kind: int, sm_scale: float = 0.0, O=None, LSE=None):
-    """Forward under the Markovian (0) or block-causal (1) mask.  Returns (O bf16, LSE fp32)."""
+    """Forward under the Markovian (0) or block-causal (1) mask; OR HMAR_SCALE_COUNTS into mask_kind
+    to give token counts per scale instead of side lengths.  Returns (O bf16, LSE fp32)."""
     lib = load_library()
     _bf16_4d("Q", Q)
     B, H, L, D = Q.shape
@@ -167,7 +172,7 @@ def hmar_attn_fwd_masked(Q, K, V, side_lens, mask_kind: int, sm_scale: float = 0
     _bf16_4d("O", O, Q.shape)
     if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, L) or not LSE.is_contiguous():
         raise HmarError("LSE must be a contiguous fp32 tensor of shape [B, H, L]")
-    arr, n, L_sched = _sides_array(side_lens)
+    arr, n, L_sched = _sides_array(side_lens, bool(int(mask_kind) & HMAR_SCALE_COUNTS))
     if L_sched != L:
         raise HmarError("sequence length does not match the scale schedule")
     with _on_device(Q.device):
@@ -204,6 +209,12 @@ def hmar_attn_bwd_workspace_bytes(side_lens, B: int, H: int, D: int) -> int:
     return int(lib.hmar_attn_bwd_workspace_bytes(arr, n, B, H, D))
 
 
+def hmar_attn_bwd_workspace_bytes_masked(side_lens, mask_kind: int, B: int, H: int, D: int) -> int:
+    lib = load_library()
+    arr, n, _ = _sides_array(side_lens, bool(int(mask_kind) & HMAR_SCALE_COUNTS))
+    return int(lib.hmar_attn_bwd_workspace_bytes_masked(arr, n, int(mask_kind), B, H, D))
+
+
 def hmar_attn_bwd(Q, K, V, O, dO, LSE, side_lens, sm_scale: float = 0.0,
                   dQ=None, dK=None, dV=None, workspace=None):
     """Backward on the tensors' device and current stream.  Returns (dQ, dK, dV) bf16."""
@@ -212,7 +223,8 @@ def hmar_attn_bwd(Q, K, V, O, dO, LSE, side_lens, sm_scale: float = 0.0,
 
 def hmar_attn_bwd_masked(Q, K, V, O, dO, LSE, side_lens, mask_kind: int, sm_scale: float = 0.0,
                          dQ=None, dK=None, dV=None, workspace=None):
-    """Backward under the Markovian (0) or block-causal (1) mask.  Returns (dQ, dK, dV) bf16."""
+    """Backward under the Markovian (0) or block-causal (1) mask (HMAR_SCALE_COUNTS as in the
+    forward).  Returns (dQ, dK, dV) bf16."""
     lib = load_library()
     _bf16_4d("Q", Q)
     B, H, L, D = Q.shape
@@ -223,11 +235,11 @@ def hmar_attn_bwd_masked(Q, K, V, O, dO, LSE, side_lens, mask_kind: int, sm_scal
     dQ = torch.empty_like(Q) if dQ is None else _bf16_4d("dQ", dQ, Q.shape)
     dK = torch.empty_like(Q) if dK is None else _bf16_4d("dK", dK, Q.shape)
     dV = torch.empty_like(Q) if dV is None else _bf16_4d("dV", dV, Q.shape)
-    arr, n, L_sched = _sides_array(side_lens)
+    arr, n, L_sched = _sides_array(side_lens, bool(int(mask_kind) & HMAR_SCALE_COUNTS))
     if L_sched != L:
         raise HmarError("sequence length does not match the scale schedule")
     if workspace is None:
-        need = int(lib.hmar_attn_bwd_workspace_bytes(arr, n, B, H, D))
+        need = int(lib.hmar_attn_bwd_workspace_bytes_masked(arr, n, int(mask_kind), B, H, D))
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
     ws_bytes = workspace.numel() * workspace.element_size()
     with _on_device(Q.device):

@@ -27,7 +27,7 @@ struct CachedSchedule {
 };
 
 std::mutex g_mu;
-// key: device, mask kind, sides (for an inference step: {n_prev, n_cur})
+// key: device, mask kind (+ the counts flag), sizes as given (for an inference step: {n_prev, n_cur})
 std::map<std::tuple<int, int32_t, std::vector<int32_t>>, std::unique_ptr<CachedSchedule>> g_cache;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -36,12 +36,15 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 hmar_status check_problem(const int32_t* side_lens, int32_t num_scales, int32_t mask_kind, int32_t B, int32_t H,
                           int32_t D, hmar::Schedule* sched) {
     if (!side_lens || num_scales < 1 || B < 1 || H < 1 || D < 1) return HMAR_ERR_INVALID_ARG;
+    if (mask_kind < 0 || (mask_kind & ~(HMAR_SCALE_COUNTS | 0xFF))) return HMAR_ERR_INVALID_ARG;
+    const bool counts = (mask_kind & HMAR_SCALE_COUNTS) != 0;
+    mask_kind &= 0xFF;
     if (mask_kind != HMAR_MASK_MARKOV && mask_kind != HMAR_MASK_BLOCK_CAUSAL) return HMAR_ERR_INVALID_ARG;
     for (int32_t k = 0; k < num_scales && k < HMAR_MAX_SCALES; ++k)
         if (side_lens[k] < 1) return HMAR_ERR_INVALID_ARG;
     if (num_scales > HMAR_MAX_SCALES) return HMAR_ERR_UNSUPPORTED;
     if (D != 64) return HMAR_ERR_UNSUPPORTED;
-    if (!hmar::build_schedule(side_lens, num_scales, mask_kind, kRowsPerItem, HMAR_MAX_SCALES, HMAR_MAX_SEQ_LEN, sched))
+    if (!hmar::build_schedule(side_lens, num_scales, counts, mask_kind, kRowsPerItem, HMAR_MAX_SCALES, HMAR_MAX_SEQ_LEN, sched))
         return HMAR_ERR_UNSUPPORTED;   // only L > HMAR_MAX_SEQ_LEN (or side > 46340) is left
     if ((int64_t)B * H > (1 << 24)) return HMAR_ERR_UNSUPPORTED;
     return HMAR_OK;
@@ -53,7 +56,7 @@ hmar_status get_device_schedule(hmar::Schedule&& host, hipStream_t stream, const
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return HMAR_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mu);
-    auto key = std::make_tuple(dev, host.mask_kind, host.sides);
+    auto key = std::make_tuple(dev, host.mask_kind | (host.sizes_are_counts ? HMAR_SCALE_COUNTS : 0), host.sides);
     auto it = g_cache.find(key);
     if (it != g_cache.end()) { *out = &it->second->dev; return HMAR_OK; }
 
@@ -222,11 +225,16 @@ hmar_status hmar_attn_step_fwd(const void* Q, const void* K, const void* V, void
     return e == hipSuccess ? HMAR_OK : HMAR_ERR_HIP;
 }
 
+size_t hmar_attn_bwd_workspace_bytes_masked(const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
+                                            int32_t B, int32_t H, int32_t D) {
+    hmar::Schedule host;
+    if (check_problem(side_lens, num_scales, mask_kind, B, H, D, &host) != HMAR_OK) return 0;
+    return 2 * (size_t)B * H * host.L * sizeof(float);
+}
+
 size_t hmar_attn_bwd_workspace_bytes(const int32_t* side_lens, int32_t num_scales,
                                      int32_t B, int32_t H, int32_t D) {
-    hmar::Schedule host;
-    if (check_problem(side_lens, num_scales, HMAR_MASK_MARKOV, B, H, D, &host) != HMAR_OK) return 0;
-    return 2 * (size_t)B * H * host.L * sizeof(float);
+    return hmar_attn_bwd_workspace_bytes_masked(side_lens, num_scales, HMAR_MASK_MARKOV, B, H, D);
 }
 
 hmar_status hmar_attn_bwd_masked(const void* Q, const void* K, const void* V, const void* O,
@@ -280,9 +288,10 @@ hmar_status hmar_schedule_describe(const int32_t* side_lens, int32_t num_scales,
 hmar_status hmar_schedule_tiles(const int32_t* side_lens, int32_t num_scales, int32_t which,
                                 int32_t* items_out, int32_t max_items, int32_t* n_items_out,
                                 int32_t* row_lo_out, int32_t* row_hi_out) {
-    // which: bit 0 = direction, bit 1 = block-causal mask instead of the Markovian one
-    if (which < 0 || which > 3 || !n_items_out || max_items < 0) return HMAR_ERR_INVALID_ARG;
-    const int32_t mask_kind = (which & 2) ? HMAR_MASK_BLOCK_CAUSAL : HMAR_MASK_MARKOV;
+    // which: bit 0 = direction, bit 1 = block-causal mask instead of the Markovian one,
+    // bit 2 = the sizes are token counts instead of side lengths
+    if (which < 0 || which > 7 || !n_items_out || max_items < 0) return HMAR_ERR_INVALID_ARG;
+    const int32_t mask_kind = ((which & 2) ? HMAR_MASK_BLOCK_CAUSAL : HMAR_MASK_MARKOV) | ((which & 4) ? HMAR_SCALE_COUNTS : 0);
     which &= 1;
     hmar::Schedule host;
     hmar_status st = check_problem(side_lens, num_scales, mask_kind, 1, 1, 64, &host);

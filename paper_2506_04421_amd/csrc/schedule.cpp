@@ -34,18 +34,19 @@ static void partition_rows(const Schedule& s, int32_t rows_per_item, std::vector
     flush();
 }
 
-bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t mask_kind, int32_t rows_per_item,
-                    int32_t max_scales, int64_t max_len, Schedule* out) {
+bool build_schedule(const int32_t* sides, int32_t num_scales, bool sizes_are_counts, int32_t mask_kind,
+                    int32_t rows_per_item, int32_t max_scales, int64_t max_len, Schedule* out) {
     if (!sides || num_scales < 1 || num_scales > max_scales || rows_per_item < 32 || rows_per_item % 32) return false;
     if (mask_kind != kMaskMarkov && mask_kind != kMaskBlockCausal) return false;
     Schedule s;
     s.mask_kind = mask_kind;
+    s.sizes_are_counts = sizes_are_counts;
     s.sides.assign(sides, sides + num_scales);
     s.off.assign(1, 0);
     int64_t L = 0;
     for (int k = 0; k < num_scales; ++k) {
-        if (sides[k] < 1 || sides[k] > 46340) return false;
-        L += (int64_t)sides[k] * sides[k];
+        if (sides[k] < 1 || (!sizes_are_counts && sides[k] > 46340)) return false;
+        L += sizes_are_counts ? (int64_t)sides[k] : (int64_t)sides[k] * sides[k];
         if (L > max_len) return false;
         s.off.push_back((int32_t)L);
     }

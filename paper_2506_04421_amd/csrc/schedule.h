@@ -26,9 +26,10 @@ struct TileItem {
 enum MaskKind : int32_t { kMaskMarkov = 0, kMaskBlockCausal = 1, kMaskStep = 2 };
 
 struct Schedule {
-    std::vector<int32_t> sides;      // for kMaskStep: {n_prev, n_cur} (token counts, not sides)
+    std::vector<int32_t> sides;      // as given: side lengths or token counts; for kMaskStep {n_prev, n_cur}
+    bool sizes_are_counts = false;   // the entries of `sides` are token counts n_k, not side lengths
     int32_t mask_kind = kMaskMarkov;
-    std::vector<int32_t> off;        // K+1 prefix sums of side^2
+    std::vector<int32_t> off;        // K+1 prefix sums of the token counts n_k
     int32_t L = 0;                   // rows of Q, O, LSE per head
     int32_t Lk = 0;                  // rows of K, V per head (= L except for kMaskStep)
     int64_t allowed_pairs = 0;       // sum_k n_k (n_{k-1} + n_k)
@@ -37,10 +38,12 @@ struct Schedule {
     std::vector<int32_t> row_lo[2], row_hi[2];   // L entries each
 };
 
-// rows_per_item: most rows one workgroup owns (a multiple of 32).  Returns false when
-// the sides are invalid (non-positive, too many, or L beyond max_len).
-bool build_schedule(const int32_t* sides, int32_t num_scales, int32_t mask_kind, int32_t rows_per_item,
-                    int32_t max_scales, int64_t max_len, Schedule* out);
+// sizes: per scale the side length s_k (n_k = s_k^2 tokens, square token maps) or, with
+// sizes_are_counts, the token count n_k itself (the paper's scales are H_k x W_k maps, Sec. 2).
+// rows_per_item: most rows one workgroup owns (a multiple of 32).  Returns false when the
+// sizes are invalid (non-positive, too many, or L beyond max_len).
+bool build_schedule(const int32_t* sizes, int32_t num_scales, bool sizes_are_counts, int32_t mask_kind,
+                    int32_t rows_per_item, int32_t max_scales, int64_t max_len, Schedule* out);
 
 // One inference step: n_cur query rows, each pairing with all n_prev + n_cur key rows.
 // Only direction 0 is filled.

@@ -304,6 +304,50 @@ def test_block_causal_mask_variant(sides):
         assert not torch.equal(Om, O)
 
 
+@pytest.mark.parametrize("counts", [(2, 6, 12, 20), (1, 3, 3, 7), (130, 70, 300), (1, 2, 6, 12, 20, 30, 56, 90, 156, 240)],
+                         ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("kind", ["markov", "block_causal"])
+def test_scales_given_as_token_counts(counts, kind):
+    # scales as H_k x W_k token maps that need not be square (Sec. 2): the sizes are token
+    # counts; the last schedule is 1x1, 1x2, 2x3, ... , 12x13, 15x16
+    L = sum(counts)
+    B, H, D = 1, 3, 64
+    Q, K, V, dO = si.draw((B, H, L, D), seed=300 + L, n_tensors=4)
+    d = _dev()
+    q, k, v, g = (t.to(d) for t in (Q, K, V, dO))
+    if kind == "markov":
+        flag, mask = hm.HMAR_MASK_MARKOV | hm.HMAR_SCALE_COUNTS, orc.markov_mask_from_counts(counts)
+    else:
+        flag, mask = hm.HMAR_MASK_BLOCK_CAUSAL | hm.HMAR_SCALE_COUNTS, orc.block_causal_mask_from_counts(counts)
+    O, LSE = hm.hmar_attn_fwd_masked(q, k, v, counts, flag)
+    dQ, dK, dV = hm.hmar_attn_bwd_masked(q, k, v, O, g, LSE, counts, flag)
+    torch.cuda.synchronize()
+    ref = {n: [] for n in ("O", "LSE", "dQ", "dK", "dV")}
+    for hh in range(H):
+        q64, k64, v64, g64 = (si.to_f64(t[0, hh]) for t in (Q, K, V, dO))
+        o, lse, _ = orc.attn_fwd_masked(q64, k64, v64, mask, 0.125)
+        a, b, c = orc.attn_bwd_masked(q64, k64, v64, g64, mask, 0.125)
+        for n, x in zip(("O", "LSE", "dQ", "dK", "dV"), (o, lse, a, b, c)):
+            ref[n].append(x)
+    ref = {n: np.stack(x) for n, x in ref.items()}
+    _compare(dict(O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV), ref, [(0, hh) for hh in range(H)], f"counts {counts} {kind}")
+
+
+def test_counts_of_square_scales_give_the_same_bits_as_side_lengths():
+    w = si.WORKLOADS["tiny"]
+    Q, K, V, dO = si.make_inputs(w)
+    d = _dev()
+    q, k, v, g = (t.to(d) for t in (Q, K, V, dO))
+    counts = [s * s for s in w.sides]
+    O1, L1 = hm.hmar_attn_fwd(q, k, v, w.sides)
+    O2, L2 = hm.hmar_attn_fwd_masked(q, k, v, counts, hm.HMAR_SCALE_COUNTS)
+    g1 = hm.hmar_attn_bwd(q, k, v, O1, g, L1, w.sides)
+    g2 = hm.hmar_attn_bwd_masked(q, k, v, O2, g, L2, counts, hm.HMAR_SCALE_COUNTS)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    assert all(torch.equal(a, b) for a, b in zip(g1, g2))
+
+
 @pytest.mark.parametrize("n_prev,n_cur", [(0, 1), (1, 4), (25, 36), (100, 169), (169, 256), (7, 130), (300, 33)])
 def test_inference_step_forward(n_prev, n_cur):
     # one KV-cache-free step (Sec. 3.1): n_cur queries against the predecessor block + themselves

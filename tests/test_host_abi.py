@@ -177,3 +177,43 @@ def test_step_and_masked_entry_points_reject_bad_arguments():
     assert lib.hmar_attn_step_fwd(*p, 4, 9, 1, 1, 32, 0.0, None) == 2
     assert lib.hmar_attn_step_fwd(None, *p[1:], 4, 9, 1, 1, 64, 0.0, None) == 1
     assert lib.hmar_attn_step_fwd(*p, 1 << 20, 9, 1, 1, 64, 0.0, None) == 2           # beyond HMAR_MAX_SEQ_LEN
+
+
+COUNT_SCHEDULES = [(2, 6, 12, 20), (1, 3, 3, 7), (5,), (130, 70, 300), (1, 2, 6, 12, 20, 30, 56, 90, 156, 240)]
+
+
+@pytest.mark.parametrize("counts", COUNT_SCHEDULES)
+@pytest.mark.parametrize("which", [0, 1, 2, 3])
+def test_tile_schedule_for_token_counts_covers_exactly_the_mask(counts, which):
+    # `which` + 4: the sizes are token counts of scales that need not be square (Sec. 2)
+    mask = orc.block_causal_mask_from_counts(counts) if which & 2 else orc.markov_mask_from_counts(counts)
+    if which & 1:
+        mask = mask.T
+    L = mask.shape[0]
+    items, lo, hi = hm.hmar_schedule_tiles(counts, which + 4)
+    assert len(lo) == L
+    rebuilt = np.zeros_like(mask)
+    for r in range(L):
+        rebuilt[r, lo[r]:hi[r]] = True
+    assert np.array_equal(rebuilt, mask)
+    owned = np.zeros(L, dtype=int)
+    for (b, e, ob, oe) in items:
+        assert 0 <= b < e <= L and e - b <= 128 and ob == min(lo[b:e]) and oe == max(hi[b:e])
+        owned[b:e] += 1
+    assert (owned == 1).all()
+    assert all(lo[r] <= lo[r + 1] and hi[r] <= hi[r + 1] for r in range(L - 1))
+
+
+def test_counts_flag_in_the_entry_points():
+    lib = hm.load_library()
+    counts = (ctypes.c_int32 * 3)(2, 6, 12)
+    p = [0x1000 * (i + 1) for i in range(5)]
+    # 20 rows with counts, 4 + 36 + 144 = 184 rows with the same numbers read as sides
+    assert hm.hmar_attn_bwd_workspace_bytes_masked((2, 6, 12), hm.HMAR_SCALE_COUNTS, 2, 3, 64) == 2 * (2 * 3 * 20 * 4)
+    assert hm.hmar_attn_bwd_workspace_bytes_masked((2, 6, 12), hm.HMAR_MASK_MARKOV, 2, 3, 64) == 2 * (2 * 3 * 184 * 4)
+    assert hm.hmar_attn_bwd_workspace_bytes_masked((2, 6, 12), hm.HMAR_MASK_BLOCK_CAUSAL | hm.HMAR_SCALE_COUNTS, 1, 1, 64) == 2 * 20 * 4
+    assert hm.hmar_attn_bwd_workspace_bytes_masked((2, 6, 12), 0x200, 1, 1, 64) == 0          # unknown flag
+    assert lib.hmar_attn_fwd_masked(*p, counts, 3, 0x200, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_fwd_masked(*p, counts, 3, hm.HMAR_SCALE_COUNTS | 5, 1, 1, 64, 0.0, None) == 1
+    big = (ctypes.c_int32 * 2)(1 << 20, 1)                                                      # L beyond HMAR_MAX_SEQ_LEN
+    assert lib.hmar_attn_fwd_masked(*p, big, 2, hm.HMAR_SCALE_COUNTS, 1, 1, 64, 0.0, None) == 2

@@ -79,6 +79,37 @@ def test_mask_equals_independent_interval_construction(sides):
     assert np.array_equal(mask, expect)
 
 
+@pytest.mark.parametrize("counts", [(2, 6, 12, 20), (1, 3, 3, 7), (5,), (4, 9, 16)])
+def test_masks_from_token_counts(counts):
+    # scales as H_k x W_k maps that need not be square (Sec. 2): (2,6,12,20) = 1x2, 2x3, 3x4, 4x5.
+    # catches: counts squared by mistake, predecessor taken two scales back, missing own block
+    L = sum(counts)
+    offs = [0]
+    for n in counts:
+        offs.append(offs[-1] + n)
+    markov = np.zeros((L, L), dtype=bool)
+    causal = np.zeros((L, L), dtype=bool)
+    for k in range(len(counts)):
+        for i in range(offs[k], offs[k + 1]):
+            for j in range(L):
+                markov[i, j] = offs[max(k - 1, 0)] <= j < offs[k + 1]
+                causal[i, j] = j < offs[k + 1]
+    assert np.array_equal(orc.markov_mask_from_counts(counts), markov)
+    assert np.array_equal(orc.block_causal_mask_from_counts(counts), causal)
+    # row sums: n_{k-1} + n_k keys per row of scale k
+    rows = orc.markov_mask_from_counts(counts).sum(axis=1)
+    for k in range(len(counts)):
+        assert (rows[offs[k]:offs[k + 1]] == counts[k] + (counts[k - 1] if k else 0)).all()
+
+
+def test_masks_from_counts_reduce_to_the_square_case():
+    for sides in (si.SIDES_TINY, (2, 5), si.SIDES_256):
+        counts = [s * s for s in sides]
+        assert np.array_equal(orc.markov_mask_from_counts(counts), orc.markov_mask(sides))
+        assert np.array_equal(orc.block_causal_mask_from_counts(counts), orc.block_causal_mask(sides))
+        assert np.array_equal(orc.scale_ids_from_counts(counts), orc.token_scale_ids(sides))
+
+
 def test_mask_row_and_column_counts_and_contiguity():
     sides = si.SIDES_256
     n = [s * s for s in sides]
