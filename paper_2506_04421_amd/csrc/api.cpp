@@ -96,6 +96,12 @@ hmar_status get_device_schedule(hmar::Schedule&& host, hipStream_t stream, const
     }
     cs->dev.L = s.L;
     cs->dev.Lk = s.Lk;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+        (void)hipFree(cs->blob);
+        return HMAR_ERR_HIP;
+    }
+    cs->dev.num_cus = cus;
     *out = &cs->dev;
     g_cache.emplace(std::move(key), std::move(cs));
     return HMAR_OK;

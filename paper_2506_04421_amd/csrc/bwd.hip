@@ -30,6 +30,7 @@ struct BwdParams {
     __bf16* dQ; __bf16* dK; __bf16* dV;
     const Item* items; const int32_t* row_lo; const int32_t* row_hi;
     int n_items, n_heads, L;
+    int tail_groups;  // see map_workgroup
     float c;          // sm_scale * log2(e)
     float sm_scale;
 };
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
     __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
 
     int head, item_id;
-    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id, true)) return;
+    if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id, true)) return;
     const Item it = p.items[item_id];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
@@ -180,7 +181,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     __shared__ __attribute__((aligned(256))) float delta_s[2][kTile];
 
     int head, item_id;
-    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
+    if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id)) return;
     const Item it = p.items[item_id];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
@@ -368,6 +369,7 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
         p.row_lo = s.row_lo[dir];
         p.row_hi = s.row_hi[dir];
         p.n_items = s.n_items[dir];
+        p.tail_groups = tail_groups_for(s.num_cus, s.n_items[dir]);
         const long long groups = 8LL * ((n_heads + 7) / 8) * s.n_items[dir];
         if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
         const int kid = dir == 1 ? kKernelDkDv : kKernelDq;

@@ -61,17 +61,29 @@ typedef const __attribute__((address_space(1))) void global_void;
 
 // Workgroup -> (head, item).  Workgroups are handed to the 8 XCDs round-robin, so all
 // items of one head are given ids that are congruent mod 8: they then run on one XCD and
-// share its L2 for the rows they re-read.  With `reverse` the heads are walked from the last
-// to the first: a kernel that follows another one over the same tensors then starts on the
-// heads that kernel touched last, which are the ones still in the last-level cache.
-__device__ __forceinline__ bool map_workgroup(int n_items, int n_heads, int* head, int* item, bool reverse = false) {
+// share its L2 for the rows they re-read.  A group is 8 heads, one per XCD.
+//  - The ids walk the groups one after the other, a group's items heaviest first, except for
+//    the last `tail_groups` groups, which form one batch walked item by item (all their
+//    heaviest items, then the next, ...): the launch then ends on the lightest items, and the
+//    period in which the device drains is as short as those.  The batch is sized to about one
+//    round of resident workgroups, small enough for its heads' K and V to share the L2.
+//  - With `reverse` the groups are walked from the last to the first: a kernel that follows
+//    another one over the same tensors then starts on the heads that kernel touched last,
+//    which are the ones still in the last-level cache.
+__device__ __forceinline__ bool map_workgroup(int n_items, int n_heads, int tail_groups, int* head, int* item,
+                                              bool reverse = false) {
     const int wg = blockIdx.x;
     const int xcd = wg & 7;
     const int slot = wg >> 3;
-    int group = slot / n_items;
-    if (reverse) group = (n_heads + 7) / 8 - 1 - group;
+    const int n_groups = (n_heads + 7) / 8;
+    const int tail = min(max(tail_groups, 1), n_groups);
+    const int head_major = (n_groups - tail) * n_items;       // slots before the tail batch
+    int group, it;
+    if (slot < head_major) { group = slot / n_items; it = slot % n_items; }
+    else { const int s2 = slot - head_major; it = s2 / tail; group = n_groups - tail + s2 % tail; }
+    if (reverse) group = n_groups - 1 - group;
     *head = group * 8 + xcd;
-    *item = slot % n_items;
+    *item = it;
     return *head < n_heads;
 }
 

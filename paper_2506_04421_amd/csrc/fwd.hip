@@ -20,6 +20,7 @@ struct FwdParams {
     __bf16* O; float* LSE;
     const Item* items; const int32_t* row_lo; const int32_t* row_hi;
     int n_items, n_heads;
+    int tail_groups;   // see map_workgroup
     int L, Lk;   // rows per head of Q/O/LSE and of K/V (they differ only for an inference step)
     float c;   // sm_scale * log2(e): scores are exponentiated in base 2
 };
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
     __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
 
     int head, item_id;
-    if (!map_workgroup(p.n_items, p.n_heads, &head, &item_id)) return;
+    if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id)) return;
     const Item it = p.items[item_id];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
@@ -183,6 +184,7 @@ hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, floa
     p.row_hi = s.row_hi[0];
     p.n_items = s.n_items[0];
     p.n_heads = n_heads;
+    p.tail_groups = tail_groups_for(s.num_cus, s.n_items[0]);
     p.L = s.L;
     p.Lk = s.Lk;
     p.c = sm_scale * kLog2e;
