@@ -39,15 +39,20 @@ def _oracle_heads(Q, K, V, dO, sides, sm_scale, heads):
 
 
 def _gpu_run(Q, K, V, dO, sides, sm_scale, backward=True):
+    # outputs start as NaN: a row that no workgroup writes shows up in the finiteness checks
     d = _dev()
     q, k, v = (t.to(d) for t in (Q, K, V))
-    O, LSE = hm.hmar_attn_fwd(q, k, v, sides, sm_scale)
+    nan_like = lambda t: torch.full_like(t, float("nan"))
+    O, LSE = hm.hmar_attn_fwd(q, k, v, sides, sm_scale, O=nan_like(q),
+                              LSE=torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device=d))
     res = {"O": O, "LSE": LSE}
     if backward:
         g = dO.to(d)
-        dQ, dK, dV = hm.hmar_attn_bwd(q, k, v, O, g, LSE, sides, sm_scale)
+        dQ, dK, dV = hm.hmar_attn_bwd(q, k, v, O, g, LSE, sides, sm_scale, dQ=nan_like(q), dK=nan_like(q), dV=nan_like(q))
         res.update(dQ=dQ, dK=dK, dV=dV)
     torch.cuda.synchronize()
+    for name, t in res.items():
+        assert torch.isfinite(t.float()).all(), f"{name}: a row was left unwritten or is not finite"
     return res
 
 
