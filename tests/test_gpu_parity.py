@@ -137,6 +137,21 @@ def test_ragged_and_degenerate_schedules(sides):
     _compare(res, _oracle_heads(Q, K, V, dO, sides, 1.0 / math.sqrt(D), heads), heads, str(sides))
 
 
+@pytest.mark.parametrize("sides,B,H", [((64,), 1, 2), ((40, 50), 1, 2), (si.SIDES_256, 1, 1), (si.SIDES_TINY, 1, 1),
+                                       ((3, 30, 4, 31), 1, 9), (si.SIDES_512, 1, 1)],
+                         ids=["one-scale-4096", "two-scales-4100", "256px-one-head", "tiny-one-head",
+                              "alternating-9-heads", "512px-one-head"])
+def test_long_scales_and_head_counts_off_the_xcd_grid(sides, B, H):
+    # scales of thousands of tokens (dozens of items per head, long key streams), a single
+    # head (7 of 8 workgroup classes idle) and a head count that is not a multiple of 8
+    L = sum(s * s for s in sides)
+    D = 64
+    Q, K, V, dO = si.draw((B, H, L, D), seed=400 + L + H, n_tensors=4)
+    res = _gpu_run(Q, K, V, dO, sides, 0.0)
+    heads = _all_heads(B, H) if L < 3000 else [(0, 0), (0, H - 1)]
+    _compare(res, _oracle_heads(Q, K, V, dO, sides, 1.0 / math.sqrt(D), heads), heads, f"{sides} B{B} H{H}")
+
+
 @pytest.mark.parametrize("name,n_heads", [("256px_b16_h16", 10), ("256px_b32_h24", 8), ("256px_b32_h30", 4),
                                           ("512px_b8_h24", 3)])
 def test_full_size_workloads_on_sampled_heads(name, n_heads):
