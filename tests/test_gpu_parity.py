@@ -188,6 +188,28 @@ def test_large_scores_exercise_the_running_maximum():
              grad_bounds=_operand_rounding_bounds(Q, K, V, dO, sides, 0.125, heads, ref))
 
 
+def test_scores_that_jump_far_above_the_first_tile():
+    # Keys late in every window are scaled so that their scores exceed the earlier ones by
+    # hundreds of binades: the reference maximum fixed on the first tiles must be raised and the
+    # accumulated output rescaled by factors that underflow to zero.  Forward only (the backward
+    # never tracks a maximum).
+    sides = si.SIDES_256
+    L, B, H, D = 680, 1, 3, 64
+    Q, K, V, _ = si.draw((B, H, L, D), seed=11, n_tensors=4)
+    offs = orc.scale_offsets(sides)
+    boost = torch.ones(L)
+    for k in range(len(sides)):                     # the last third of every scale's keys
+        a, b = offs[k], offs[k + 1]
+        boost[b - max((b - a) // 3, 1):b] = 64.0
+    K = (K.float() * boost.view(1, 1, L, 1)).to(torch.bfloat16)
+    Q = (Q.float() * 8.0).to(torch.bfloat16)        # raw scores up to ~ 8 * 64 * 8 * few = thousands
+    res = _gpu_run(Q, K, V, None, sides, 0.125, backward=False)
+    heads = _all_heads(B, H)
+    ref = _oracle_heads(Q, K, V, None, sides, 0.125, heads)
+    _compare(res, ref, heads, "late-dominant-keys")
+    assert float(np.abs(ref["LSE"]).max()) > 300.0  # the case really is extreme
+
+
 def test_custom_softmax_scale():
     sides = (3, 6, 9)
     L, B, H, D = 126, 1, 2, 64
