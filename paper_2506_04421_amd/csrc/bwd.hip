@@ -167,10 +167,9 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 }
 
 // ---------------------------------------------------------------------------------- dK, dV
-// Register budget: 3 wavefronts per SIMD (168 VGPRs) hides more latency than 2 with a
-// roomier allocation; measured on the 256px training shape.
-// Its register footprint, not LDS, limits this kernel to two workgroups per CU, so it can
-// afford a deeper ring than the other kernels.
+// Register budget: the two result accumulators, the own K and V rows and the batched LDS
+// operands need about 220 VGPRs, which means two wavefronts per SIMD (two workgroups per CU);
+// without the batching it would still need about 190, more than the 168 that three allow.
 #ifndef HMAR_DKDV_MIN_WAVES
 #define HMAR_DKDV_MIN_WAVES 2
 #endif

@@ -245,12 +245,6 @@ __device__ __forceinline__ bf16x8 lds_a_tr(uint32_t tile, const LaneOffsets& o, 
     return __builtin_bit_cast(bf16x8, v);
 }
 
-// sum of the two bf16 halves of a packed pair, added to acc (v_dot2c_f32_bf16 with ones)
-__device__ __forceinline__ float add_pair_bf16(uint32_t packed, float acc) {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed),
-                                           __builtin_bit_cast(bf16x2, 0x3F803F80u), acc, false);
-}
-
 // Mask one 32 x 32 score block held in the C layout.  Register i of the lane is the
 // streamed row (key in the forward and dQ kernels, query in the dK/dV kernel) with index
 // c0 + 8*(i/4) + i%4 relative to the lane's base row; entries whose relative index lies
