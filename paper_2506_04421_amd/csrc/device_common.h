@@ -29,7 +29,6 @@
 namespace hmar {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -99,15 +98,6 @@ __device__ __forceinline__ float half_max(float x) {
 __device__ __forceinline__ float half_sum(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-__device__ __forceinline__ int wave_min(int x) {
-    for (int o = 32; o > 0; o >>= 1) x = min(x, __shfl_xor(x, o));
-    return __builtin_amdgcn_readfirstlane(x);
-}
-__device__ __forceinline__ int wave_max(int x) {
-    for (int o = 32; o > 0; o >>= 1) x = max(x, __shfl_xor(x, o));
-    return __builtin_amdgcn_readfirstlane(x);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -260,12 +250,6 @@ __device__ __forceinline__ void mask_block(f32x16& s, int c0, int lim_lo, int li
 #pragma unroll
         for (int i = 0; i < 16; ++i) s[i] = (c0 + 8 * (i >> 2) + (i & 3)) >= lim_lo ? s[i] : -INFINITY;
     }
-}
-
-// store 4 consecutive fp32 of one output row as bf16 (8 bytes)
-__device__ __forceinline__ void store4_bf16(__bf16* dst, float a, float b, float c, float d) {
-    u32x2 u = {pack_bf16(a, b), pack_bf16(c, d)};
-    *reinterpret_cast<u32x2*>(dst) = u;
 }
 
 // Write a wavefront's result block to global memory as bf16 rows.  The block is the pair of
