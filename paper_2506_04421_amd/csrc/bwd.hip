@@ -35,9 +35,6 @@ struct BwdParams {
     float sm_scale;
 };
 
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-
 // ------------------------------------------------------------------------------------- dQ
 #ifndef HMAR_DQ_MIN_WAVES
 #define HMAR_DQ_MIN_WAVES 4
@@ -89,10 +86,13 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         float acc = 0.f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const u32x4 ov = *reinterpret_cast<const u32x4*>(p.O + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
-            const u32x4 gv = __builtin_bit_cast(u32x4, dob[t]);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc += bf16_lo(ov[i]) * bf16_lo(gv[i]) + bf16_hi(ov[i]) * bf16_hi(gv[i]);
+            const bf16x8 ov = *reinterpret_cast<const bf16x8*>(p.O + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
+            const bf16x8 gv = dob[t];
+            // two products per instruction (v_dot2c_f32_bf16), fp32 accumulation
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 0, 1), __builtin_shufflevector(gv, gv, 0, 1), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 2, 3), __builtin_shufflevector(gv, gv, 2, 3), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 4, 5), __builtin_shufflevector(gv, gv, 4, 5), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 6, 7), __builtin_shufflevector(gv, gv, 6, 7), acc, false);
         }
         ndelta = -half_sum(acc);
     }
