@@ -19,7 +19,9 @@
  *  - Calls enqueue work on `stream` (a hipStream_t, may be null for the default stream)
  *    and return without synchronising.  A small per-schedule device table is built on the
  *    first use of a schedule on a device and cached for the life of the process (this is
- *    the only allocation the library makes; the cache is thread-safe).
+ *    the only allocation the library makes; the cache is thread-safe).  That first use
+ *    allocates and copies synchronously: make it outside a HIP stream capture; later calls
+ *    with the same schedule only launch kernels and may be captured into a graph.
  *  - Errors are return codes.  Argument checks happen before any device work.
  *  - Inputs must be finite.  Rounding: products accumulate in fp32; the softmax
  *    probabilities (and, in the backward, dS) are rounded to bf16 before the second
