@@ -278,6 +278,18 @@ def main() -> int:
     fwd_ms = timed(fwd)
     bwd_ms = timed(bwd)
 
+    # spread of the individual repetitions: one HIP event between consecutive calls
+    def spread(fn, n=50):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record()
+        for i in range(n):
+            fn(sets[i % len(sets)])
+            ev[i + 1].record()
+        ev[n].synchronize()
+        t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
+        return {"median_ms": t[n // 2], "min_ms": t[0], "max_ms": t[-1], "n": n}
+    spreads = {"fwd": spread(fwd), "bwd": spread(bwd), "fwd_bwd": spread(lambda s_: (fwd(s_), bwd(s_)))}
+
     # per-kernel durations: the same steps again with every launch bracketed by HIP events
     hm.hmar_profile_begin()
     for i in range(args.steps):
@@ -321,7 +333,7 @@ def main() -> int:
                    "spin_up_ms": args.spin_up_ms},
         "ms_per_step_eager": ms_eager, "ms_per_step_graph": ms_graph,
         "pct_mfma_peak": 100.0 * value / MFMA_PEAK_TFLOPS,
-        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "repetition_spread": spreads,
         "fwd_tflops": flops_fwd / (fwd_ms * 1e-3) / 1e12, "bwd_tflops": flops_bwd / (bwd_ms * 1e-3) / 1e12,
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kern_ms,
