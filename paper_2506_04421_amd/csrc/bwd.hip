@@ -167,9 +167,10 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 }
 
 // ---------------------------------------------------------------------------------- dK, dV
-// Register budget: the two result accumulators, the own K and V rows and the batched LDS
-// operands need about 220 VGPRs, which means two wavefronts per SIMD (two workgroups per CU);
-// without the batching it would still need about 190, more than the 168 that three allow.
+// Register budget: the two result accumulators, the own K and V rows, both blocks' scores and
+// the batched LDS operands need about 250 VGPRs, which means two wavefronts per SIMD (two
+// workgroups per CU); the leanest form of the kernel would still need about 190, more than
+// the 168 that three wavefronts allow.
 #ifndef HMAR_DKDV_MIN_WAVES
 #define HMAR_DKDV_MIN_WAVES 2
 #endif
@@ -244,12 +245,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
             const uint32_t delta_t = delta_base + ST * (kTile * 4) + 16 * h;
             const bool need_lo = qt < full_lo, need_hi = qt + kTile > full_hi;
             const int lim_lo = lo - qt - 4 * h, lim_hi = hi - qt - 4 * h;
+            // Operands are fetched from LDS in batches ahead of the contractions that use them
+            // (the scheduling barriers keep the compiler from sinking each read next to its use,
+            // which would expose the LDS latency once per matrix instruction).  The score and dP
+            // contractions of both 32-query blocks are issued first, so that the matrix pipe works
+            // on the second block while the vector units form the first block's probabilities.
+            f32x16 s[2], dp[2];
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                // Operands are fetched from LDS in batches ahead of the contractions that use
-                // them (the scheduling barriers keep the compiler from sinking each read next to
-                // its use, which would expose the LDS latency once per matrix instruction).
-                f32x16 s, dp;
                 bf16x8 aq[4], ag[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -262,14 +265,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
                 for (int j = 0; j < 4; ++j) {
                     const f32x4 d4 = *(lds_f32x4*)(delta_t + (32 * qb + 8 * j) * 4);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) { s[4 * j + r] = 0.f; dp[4 * j + r] = d4[r]; }
+                    for (int r = 0; r < 4; ++r) { s[qb][4 * j + r] = 0.f; dp[qb][4 * j + r] = d4[r]; }
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    s = mfma32(aq[t], kreg[t], s);
-                    dp = mfma32(ag[t], vreg[t], dp);
+                    s[qb] = mfma32(aq[t], kreg[t], s[qb]);
+                    dp[qb] = mfma32(ag[t], vreg[t], dp[qb]);
                 }
+            }
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
                 // transposed operands of the second pair of contractions and the row statistics,
                 // requested before the exponentials so that their latency hides behind them
                 bf16x8 tg[2][2], tq[2][2];
@@ -284,23 +290,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
                         tq[sub][mb] = lds_a_tr(Qt, lo_, mb, 2 * qb + sub);
                     }
                 __builtin_amdgcn_sched_barrier(0);
-                mask_block(s, 32 * qb, lim_lo, lim_hi, need_lo, need_hi);
+                mask_block(s[qb], 32 * qb, lim_lo, lim_hi, need_lo, need_hi);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int i = 4 * j + r;
-                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.c, l4[j][r]));
-                        s[i] = pv;
-                        dp[i] = pv * dp[i];
+                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][i], p.c, l4[j][r]));
+                        s[qb][i] = pv;
+                        dp[qb][i] = pv * dp[qb][i];
                     }
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub) {
                     const int e0 = 8 * sub;
-                    const bf16x8 pb = pack8(s[e0 + 0], s[e0 + 1], s[e0 + 2], s[e0 + 3],
-                                            s[e0 + 4], s[e0 + 5], s[e0 + 6], s[e0 + 7]);
-                    const bf16x8 dsb = pack8(dp[e0 + 0], dp[e0 + 1], dp[e0 + 2], dp[e0 + 3],
-                                             dp[e0 + 4], dp[e0 + 5], dp[e0 + 6], dp[e0 + 7]);
+                    const bf16x8 pb = pack8(s[qb][e0 + 0], s[qb][e0 + 1], s[qb][e0 + 2], s[qb][e0 + 3],
+                                            s[qb][e0 + 4], s[qb][e0 + 5], s[qb][e0 + 6], s[qb][e0 + 7]);
+                    const bf16x8 dsb = pack8(dp[qb][e0 + 0], dp[qb][e0 + 1], dp[qb][e0 + 2], dp[qb][e0 + 3],
+                                             dp[qb][e0 + 4], dp[qb][e0 + 5], dp[qb][e0 + 6], dp[qb][e0 + 7]);
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb) {
                         dv[mb] = mfma32(tg[sub][mb], pb, dv[mb]);
