@@ -286,6 +286,49 @@ def test_runs_on_a_side_stream():
              _oracle_heads(Q, K, V, dO, w.sides, 0.125, heads), heads, "side-stream")
 
 
+def test_concurrent_first_use_of_schedules_from_several_threads():
+    # the per-schedule device tables are built on first use under a lock: four host threads,
+    # each on its own stream, each starting with schedules nobody has used yet, must get the
+    # same bits a single thread gets afterwards
+    import threading
+    schedules = [(2, 3, 4, 9), (5, 1, 6), (11,), (3, 3, 3, 3, 3), (1, 2, 4, 8), (7, 2, 7), (4, 4), (10, 1)]
+    B, H, D = 1, 2, 64
+    d = _dev()
+    inputs = {}
+    for sides in schedules:
+        L = sum(x * x for x in sides)
+        inputs[sides] = tuple(t.to(d) for t in si.draw((B, H, L, D), seed=500 + L, n_tensors=4))
+    results, errors = {}, []
+
+    def worker(idx):
+        try:
+            stream = torch.cuda.Stream(device=d)
+            with torch.cuda.stream(stream):
+                for sides in schedules[idx::4] + schedules:          # own first uses, then everybody's
+                    q, k, v, g = inputs[sides]
+                    O, LSE = hm.hmar_attn_fwd(q, k, v, sides)
+                    grads = hm.hmar_attn_bwd(q, k, v, O, g, LSE, sides)
+                    stream.synchronize()
+                    results.setdefault((idx, sides), (O, LSE) + tuple(grads))
+        except Exception as e:                                       # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for sides in schedules:
+        q, k, v, g = inputs[sides]
+        O, LSE = hm.hmar_attn_fwd(q, k, v, sides)
+        ref = (O, LSE) + tuple(hm.hmar_attn_bwd(q, k, v, O, g, LSE, sides))
+        torch.cuda.synchronize()
+        for idx in range(4):
+            for a, b in zip(results[(idx, sides)], ref):
+                assert torch.equal(a, b), (idx, sides)
+
+
 def test_hip_graph_replays_match_eager_launches():
     # the benchmark times captured graphs: every replay must reproduce the eager result
     # bit for bit (the kernels are deterministic), with eager work in between
