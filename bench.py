@@ -81,7 +81,7 @@ def cpu_baseline(w, A: int, budget_s: float = 15.0):
     t0 = time.perf_counter()
     run()
     once = time.perf_counter() - t0
-    reps = max(1, min(50, int(budget_s / max(once, 1e-3))))
+    reps = max(1, min(200, int(budget_s / max(once, 1e-3))))
     t0 = time.perf_counter()
     for _ in range(reps):
         run()
