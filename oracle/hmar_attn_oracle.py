@@ -6,18 +6,18 @@ and never imports it.
 
 What it computes
 ----------------
-HMAR (Sec. 3.1, Eq. 4) makes next-scale prediction Markovian: the tokens of
+HMAR (Sec. "Efficient Markovian Next-Scale Prediction", Eq. 4) makes next-scale prediction Markovian: the tokens of
 resolution scale k are conditioned on one block of H_{k-1} x W_{k-1} tokens that
 stands for everything before it, instead of on all earlier scales.  During training
-the K scales are laid end to end, coarse to fine, in one sequence (Sec. 2,
+the K scales are laid end to end, coarse to fine, in one sequence (Sec. "Background",
 next-scale prediction), and the attention mask changes from VAR's lower
-block-triangular pattern to a banded block pattern (Sec. 3.1, App. B.2).  Inside a
-scale attention stays bidirectional (Sec. 2), and the refinement module conditions
-on the scale's own tokens plus the predecessor block (Sec. 3.4).  Hence
+block-triangular pattern to a banded block pattern (Sec. "Efficient Markovian Next-Scale Prediction", appendix "Attention Patterns").  Inside a
+scale attention stays bidirectional (Sec. "Background"), and the refinement module conditions
+on the scale's own tokens plus the predecessor block (Sec. "The HMAR Architecture").  Hence
 
     allowed(i, j)  <=>  scale(j) == scale(i)  or  scale(j) == scale(i) - 1 .
 
-The kernel the paper describes (Sec. 3.1, App. B.4) is an exact FlashAttention-style
+The kernel the paper describes (Sec. "Efficient Markovian Next-Scale Prediction", appendix "Efficient Attention Performance") is an exact FlashAttention-style
 evaluation of softmax attention under that mask, so the oracle is the plain
 definition written out densely with an explicit L x L mask, per (batch, head) slice:
 
@@ -54,7 +54,7 @@ __all__ = [
 
 # --------------------------------------------------------------------------- schedule
 def scale_token_counts(side_lens):
-    """n_k = s_k^2 tokens in scale k (Sec. 2: scale k holds H_k x W_k tokens; square maps)."""
+    """n_k = s_k^2 tokens in scale k (Sec. "Background": scale k holds H_k x W_k tokens; square maps)."""
     sides = [int(s) for s in side_lens]
     if len(sides) == 0 or any(s < 1 for s in sides):
         raise ValueError("side lengths must be a non-empty list of positive integers")
@@ -78,7 +78,7 @@ def token_scale_ids(side_lens):
 
 
 def markov_mask(side_lens):
-    """L x L boolean mask of the Markovian pattern (Sec. 3.1, Eq. 4; App. B.2).
+    """L x L boolean mask of the Markovian pattern (Sec. "Efficient Markovian Next-Scale Prediction", Eq. 4; appendix "Attention Patterns").
 
     Built from per-token scale ids only: a query of scale k may look at keys of scale
     k (bidirectional inside a scale) and of its immediate predecessor k-1.  Scale 1
@@ -91,14 +91,14 @@ def markov_mask(side_lens):
 
 
 def block_causal_mask(side_lens):
-    """VAR's block-causal mask (Sec. 2): scale k sees every scale <= k."""
+    """VAR's block-causal mask (Sec. "Background"): scale k sees every scale <= k."""
     sid = token_scale_ids(side_lens)
     return sid[None, :] <= sid[:, None]
 
 
 def scale_ids_from_counts(token_counts):
     """scale id (1-based) of every token when scale k holds token_counts[k-1] = H_k * W_k tokens
-    of a token map that need not be square (Sec. 2)."""
+    of a token map that need not be square (Sec. "Background")."""
     counts = [int(n) for n in token_counts]
     if len(counts) == 0 or any(n < 1 for n in counts):
         raise ValueError("token counts must be a non-empty list of positive integers")
@@ -109,13 +109,13 @@ def scale_ids_from_counts(token_counts):
 
 
 def markov_mask_from_counts(token_counts):
-    """The Markovian mask (Sec. 3.1, Eq. 4) for scales given by their token counts."""
+    """The Markovian mask (Sec. "Efficient Markovian Next-Scale Prediction", Eq. 4) for scales given by their token counts."""
     sid = scale_ids_from_counts(token_counts)
     return (sid[None, :] == sid[:, None]) | (sid[None, :] == sid[:, None] - 1)
 
 
 def block_causal_mask_from_counts(token_counts):
-    """VAR's block-causal mask (Sec. 2) for scales given by their token counts."""
+    """VAR's block-causal mask (Sec. "Background") for scales given by their token counts."""
     sid = scale_ids_from_counts(token_counts)
     return sid[None, :] <= sid[:, None]
 
@@ -184,7 +184,7 @@ def _check_shapes(side_lens, *tensors):
 
 
 def attn_fwd(Q, K, V, side_lens, sm_scale=None):
-    """Markovian next-scale attention forward (Sec. 3.1).  Q, K, V: [B, H, L, D].
+    """Markovian next-scale attention forward (Sec. "Efficient Markovian Next-Scale Prediction").  Q, K, V: [B, H, L, D].
 
     Returns (O [B,H,L,D], LSE [B,H,L]) in float64.  sm_scale defaults to 1/sqrt(D).
     """
@@ -206,7 +206,7 @@ def attn_bwd(Q, K, V, dO, side_lens, sm_scale=None):
 
 
 def attn_step_fwd(Q, K, V, n_prev, sm_scale=None):
-    """One KV-cache-free inference step (Sec. 3.1, last paragraph; Sec. 5.2).
+    """One KV-cache-free inference step (Sec. "Efficient Markovian Next-Scale Prediction", last paragraph; Sec. "Efficiency").
 
     The step that generates scale k holds only the predecessor block and the scale's
     own tokens: K, V have n_{k-1} + n_k rows (predecessor block first), Q has the

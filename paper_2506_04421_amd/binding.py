@@ -44,6 +44,11 @@ def load_library() -> ctypes.CDLL:
     lib.hmar_attn_fwd_masked.argtypes = [vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, i32, f32, vp]
     lib.hmar_attn_step_fwd.restype = ctypes.c_int
     lib.hmar_attn_step_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp]
+    pvp = ctypes.POINTER(vp)
+    lib.hmar_attn_steps_fwd.restype = ctypes.c_int
+    lib.hmar_attn_steps_fwd.argtypes = [pvp, pvp, pvp, pvp, pvp, pi32, pi32, i32, i32, i32, i32, f32, vp]
+    lib.hmar_attn_step_fwd_rows.restype = ctypes.c_int
+    lib.hmar_attn_step_fwd_rows.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, vp]
     lib.hmar_attn_bwd_masked.restype = ctypes.c_int
     lib.hmar_attn_bwd_masked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, i32, f32,
                                          vp, sz, vp]
@@ -91,13 +96,24 @@ def _sides_array(side_lens: Sequence[int], counts: bool = False):
     return hit
 
 
-def _bf16_4d(name: str, t: torch.Tensor, shape=None):
+def _bf16_4d(name: str, t: torch.Tensor, shape=None, device=None):
     if not isinstance(t, torch.Tensor) or not t.is_cuda:
         raise HmarError(f"{name} must be a device tensor")
+    if device is not None and t.device != device:
+        raise HmarError(f"{name} is on {t.device}, expected {device}: all tensors of a call share one device")
     if t.dtype != torch.bfloat16 or t.dim() != 4 or not t.is_contiguous():
         raise HmarError(f"{name} must be a contiguous bf16 tensor of shape [B, H, L, D]")
     if shape is not None and tuple(t.shape) != tuple(shape):
         raise HmarError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t
+
+
+def _f32_stats(name: str, t: torch.Tensor, shape, device):
+    """A per-row fp32 tensor (LSE): a host pointer handed to a kernel would fault the GPU."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.device != device:
+        raise HmarError(f"{name} must be a device tensor on {device}")
+    if t.dtype != torch.float32 or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+        raise HmarError(f"{name} must be a contiguous fp32 tensor of shape {tuple(shape)}")
     return t
 
 
@@ -163,15 +179,14 @@ def hmar_attn_fwd_masked(Q, K, V, side_lens, mask_kind: int, sm_scale: float = 0
     lib = load_library()
     _bf16_4d("Q", Q)
     B, H, L, D = Q.shape
-    _bf16_4d("K", K, Q.shape)
-    _bf16_4d("V", V, Q.shape)
+    _bf16_4d("K", K, Q.shape, Q.device)
+    _bf16_4d("V", V, Q.shape, Q.device)
     if O is None:
         O = torch.empty_like(Q)
     if LSE is None:
         LSE = torch.empty((B, H, L), dtype=torch.float32, device=Q.device)
-    _bf16_4d("O", O, Q.shape)
-    if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, L) or not LSE.is_contiguous():
-        raise HmarError("LSE must be a contiguous fp32 tensor of shape [B, H, L]")
+    _bf16_4d("O", O, Q.shape, Q.device)
+    _f32_stats("LSE", LSE, (B, H, L), Q.device)
     arr, n, L_sched = _sides_array(side_lens, bool(int(mask_kind) & HMAR_SCALE_COUNTS))
     if L_sched != L:
         raise HmarError("sequence length does not match the scale schedule")
@@ -182,24 +197,72 @@ def hmar_attn_fwd_masked(Q, K, V, side_lens, mask_kind: int, sm_scale: float = 0
     return O, LSE
 
 
-def hmar_attn_step_fwd(Q, K, V, n_prev: int, sm_scale: float = 0.0, O=None, LSE=None):
-    """One inference step: Q [B,H,n_cur,D] against K, V [B,H,n_prev+n_cur,D].  Returns (O, LSE)."""
-    lib = load_library()
+def _step_tensors(Q, K, V, n_prev, O, LSE):
     _bf16_4d("Q", Q)
     B, H, n_cur, D = Q.shape
-    _bf16_4d("K", K, (B, H, int(n_prev) + n_cur, D))
-    _bf16_4d("V", V, K.shape)
+    _bf16_4d("K", K, (B, H, int(n_prev) + n_cur, D), Q.device)
+    _bf16_4d("V", V, K.shape, Q.device)
     if O is None:
         O = torch.empty_like(Q)
     if LSE is None:
         LSE = torch.empty((B, H, n_cur), dtype=torch.float32, device=Q.device)
-    _bf16_4d("O", O, Q.shape)
-    if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, n_cur) or not LSE.is_contiguous():
-        raise HmarError("LSE must be a contiguous fp32 tensor of shape [B, H, n_cur]")
+    _bf16_4d("O", O, Q.shape, Q.device)
+    _f32_stats("LSE", LSE, (B, H, n_cur), Q.device)
+    return O, LSE
+
+
+def hmar_attn_step_fwd(Q, K, V, n_prev: int, sm_scale: float = 0.0, O=None, LSE=None):
+    """One inference step: Q [B,H,n_cur,D] against K, V [B,H,n_prev+n_cur,D].  Returns (O, LSE)."""
+    lib = load_library()
+    O, LSE = _step_tensors(Q, K, V, n_prev, O, LSE)
+    B, H, n_cur, D = Q.shape
     with _on_device(Q.device):
         code = lib.hmar_attn_step_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
                                       int(n_prev), n_cur, B, H, D, float(sm_scale), _stream_handle(Q))
     _check(code, "hmar_attn_step_fwd")
+    return O, LSE
+
+
+def hmar_attn_steps_fwd(Qs, Ks, Vs, n_prevs, sm_scale: float = 0.0, Os=None, LSEs=None):
+    """Several independent inference steps in one call (see hmar_attn_step_fwd for one step's
+    tensors).  Qs, Ks, Vs, n_prevs: equally long sequences.  Returns (list of O, list of LSE)."""
+    lib = load_library()
+    n = len(Qs)
+    if n < 1 or not (len(Ks) == len(Vs) == len(n_prevs) == n):
+        raise HmarError("hmar_attn_steps_fwd needs equally long, non-empty lists")
+    Os = [None] * n if Os is None else list(Os)
+    LSEs = [None] * n if LSEs is None else list(LSEs)
+    B, H, _, D = Qs[0].shape
+    for i in range(n):
+        if tuple(Qs[i].shape[:2]) != (B, H) or Qs[i].shape[3] != D or Qs[i].device != Qs[0].device:
+            raise HmarError("every step of a call has the same B, H, D and device")
+        Os[i], LSEs[i] = _step_tensors(Qs[i], Ks[i], Vs[i], n_prevs[i], Os[i], LSEs[i])
+    vp = ctypes.c_void_p * n
+    i32 = ctypes.c_int32 * n
+    with _on_device(Qs[0].device):
+        code = lib.hmar_attn_steps_fwd(vp(*[t.data_ptr() for t in Qs]), vp(*[t.data_ptr() for t in Ks]),
+                                       vp(*[t.data_ptr() for t in Vs]), vp(*[t.data_ptr() for t in Os]),
+                                       vp(*[t.data_ptr() for t in LSEs]), i32(*[int(x) for x in n_prevs]),
+                                       i32(*[int(q.shape[2]) for q in Qs]), n, B, H, D, float(sm_scale),
+                                       _stream_handle(Qs[0]))
+    _check(code, "hmar_attn_steps_fwd")
+    return Os, LSEs
+
+
+def hmar_attn_step_fwd_rows(Q, K, V, n_prev: int, rows: torch.Tensor, O, LSE, sm_scale: float = 0.0):
+    """One refinement pass inside a scale: only the query rows listed in `rows` (device int32,
+    distinct values in [0, n_cur)) are computed; the other rows of O and LSE stay as they are."""
+    lib = load_library()
+    O, LSE = _step_tensors(Q, K, V, n_prev, O, LSE)
+    B, H, n_cur, D = Q.shape
+    if (not isinstance(rows, torch.Tensor) or not rows.is_cuda or rows.device != Q.device or rows.dtype != torch.int32
+            or rows.dim() != 1 or not rows.is_contiguous() or not 1 <= rows.numel() <= n_cur):
+        raise HmarError("rows must be a contiguous device int32 vector of 1..n_cur row indices")
+    with _on_device(Q.device):
+        code = lib.hmar_attn_step_fwd_rows(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                                           rows.data_ptr(), rows.numel(), int(n_prev), n_cur, B, H, D,
+                                           float(sm_scale), _stream_handle(Q))
+    _check(code, "hmar_attn_step_fwd_rows")
     return O, LSE
 
 
@@ -229,18 +292,19 @@ def hmar_attn_bwd_masked(Q, K, V, O, dO, LSE, side_lens, mask_kind: int, sm_scal
     _bf16_4d("Q", Q)
     B, H, L, D = Q.shape
     for name, t in (("K", K), ("V", V), ("O", O), ("dO", dO)):
-        _bf16_4d(name, t, Q.shape)
-    if LSE.dtype != torch.float32 or tuple(LSE.shape) != (B, H, L) or not LSE.is_contiguous() or not LSE.is_cuda:
-        raise HmarError("LSE must be a contiguous device fp32 tensor of shape [B, H, L]")
-    dQ = torch.empty_like(Q) if dQ is None else _bf16_4d("dQ", dQ, Q.shape)
-    dK = torch.empty_like(Q) if dK is None else _bf16_4d("dK", dK, Q.shape)
-    dV = torch.empty_like(Q) if dV is None else _bf16_4d("dV", dV, Q.shape)
+        _bf16_4d(name, t, Q.shape, Q.device)
+    _f32_stats("LSE", LSE, (B, H, L), Q.device)
+    dQ = torch.empty_like(Q) if dQ is None else _bf16_4d("dQ", dQ, Q.shape, Q.device)
+    dK = torch.empty_like(Q) if dK is None else _bf16_4d("dK", dK, Q.shape, Q.device)
+    dV = torch.empty_like(Q) if dV is None else _bf16_4d("dV", dV, Q.shape, Q.device)
     arr, n, L_sched = _sides_array(side_lens, bool(int(mask_kind) & HMAR_SCALE_COUNTS))
     if L_sched != L:
         raise HmarError("sequence length does not match the scale schedule")
     if workspace is None:
         need = int(lib.hmar_attn_bwd_workspace_bytes_masked(arr, n, int(mask_kind), B, H, D))
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    elif not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or workspace.device != Q.device:
+        raise HmarError("workspace must be a device tensor on the tensors' device")
     ws_bytes = workspace.numel() * workspace.element_size()
     with _on_device(Q.device):
         code = lib.hmar_attn_bwd_masked(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),

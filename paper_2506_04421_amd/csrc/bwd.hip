@@ -1,4 +1,4 @@
-// Backward kernels of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
+// Backward kernels of the Markovian next-scale attention (paper Sec. "Efficient Markovian Next-Scale Prediction", appendix "Efficient Attention Performance") for gfx950.
 //
 //   hmar_dq_kernel    : query-stationary, same walk as the forward but over the heads in reverse
 //                       order (the forward before it and the dK/dV kernel after it both walk
@@ -162,8 +162,7 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
     }
 
     if (wave_active)
-        store_block_rows(smem_base + wave * kPatchBytes, dq, p.sm_scale, p.dQ + head_off + (size_t)wq0 * kD,
-                         it.own_end - wq0, lane);
+        store_block_rows(smem_base + wave * kPatchBytes, dq, p.sm_scale, p.dQ + head_off, wq0, it.own_end - wq0, lane);
 }
 
 // ---------------------------------------------------------------------------------- dK, dV
@@ -325,8 +324,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
 
     if (wave_active) {
         const uint32_t patch = smem_base + wave * kPatchBytes;
-        store_block_rows(patch, dk, p.sm_scale, p.dK + head_off + (size_t)wk0 * kD, it.own_end - wk0, lane);
-        store_block_rows(patch, dv, 1.0f, p.dV + head_off + (size_t)wk0 * kD, it.own_end - wk0, lane);
+        store_block_rows(patch, dk, p.sm_scale, p.dK + head_off, wk0, it.own_end - wk0, lane);
+        store_block_rows(patch, dv, 1.0f, p.dV + head_off, wk0, it.own_end - wk0, lane);
     }
 }
 

@@ -257,13 +257,14 @@ __device__ __forceinline__ void mask_block(f32x16& s, int c0, int lim_lo, int li
 // columns 32*mb + 8*(i/4) + 4h + i%4).  Storing it directly would scatter 8-byte pieces over
 // 32 rows per instruction; instead it is transposed through a private LDS patch
 // (32 rows x kPatchPitch bytes) and leaves as full 128-byte rows, 8 rows per instruction.
-// `patch` is the LDS address of this wavefront's patch, `out` points at the wavefront's
-// first row, rows >= nrows are not written.  LDS operations of one wavefront execute in
+// `patch` is the LDS address of this wavefront's patch, `out` points at row 0 of the head, the
+// wavefront's rows are row0 .. row0 + nrows - 1 (at most 32; through row_map if given).  LDS operations of one wavefront execute in
 // order, so no barrier is needed between the writes and the reads.
 constexpr int kPatchPitch = 144;                     // 128 + 16: keeps 16-byte alignment
 constexpr int kPatchBytes = 32 * kPatchPitch;        // per wavefront
 __device__ __forceinline__ void store_block_rows(uint32_t patch, const f32x16 (&acc)[2], float scale,
-                                                 __bf16* out, int nrows, int lane) {
+                                                 __bf16* out, int row0, int nrows, int lane,
+                                                 const int32_t* row_map = nullptr) {
     typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
     typedef const __attribute__((address_space(3))) u32x4 lds_u32x4;
     const int lr = lane & 31, h = lane >> 5;
@@ -279,7 +280,10 @@ __device__ __forceinline__ void store_block_rows(uint32_t patch, const f32x16 (&
     for (int i = 0; i < 4; ++i) {
         const int row = 8 * i + (lane >> 3), chunk = lane & 7;
         const u32x4 v = *(lds_u32x4*)(patch + row * kPatchPitch + chunk * 16);
-        if (row < nrows) *reinterpret_cast<u32x4*>(out + (size_t)row * kD + chunk * 8) = v;
+        if (row < nrows) {
+            const int r = row_map ? row_map[row0 + row] : row0 + row;
+            *reinterpret_cast<u32x4*>(out + (size_t)r * kD + chunk * 8) = v;
+        }
     }
 }
 

@@ -1,4 +1,5 @@
-// Forward kernel of the Markovian next-scale attention (paper Sec. 3.1, App. B.4) for gfx950.
+// Forward kernel of the Markovian next-scale attention (paper Sec. "Efficient Markovian
+// Next-Scale Prediction"; appendix "Efficient Attention Performance") for gfx950.
 //
 // One workgroup (4 wavefronts) owns up to 128 consecutive query rows, 32 per wavefront,
 // and streams the key/value rows of their two-scale windows through a two-stage ring of LDS
@@ -21,8 +22,28 @@ struct FwdParams {
     const Item* items; const int32_t* row_lo; const int32_t* row_hi;
     int n_items, n_heads;
     int tail_groups;   // see map_workgroup
-    int L, Lk;   // rows per head of Q/O/LSE and of K/V (they differ only for an inference step)
+    int L, Lk;   // rows per head of Q/O/LSE and of K/V
     float c;   // sm_scale * log2(e): scores are exponentiated in base 2
+};
+
+// Inference steps (paper Sec. "Efficient Markovian Next-Scale Prediction", last paragraph): a
+// launch covers up to kMaxSteps independent steps, each with its own buffers; every query row
+// of a step pairs with all of the step's key rows, so no table is needed: item i of a step owns
+// query rows [128 i, 128 (i+1)) and visits keys [0, Lk).  The descriptors travel by value in
+// the kernel arguments, sorted by decreasing work (the launch then ends on the lightest step).
+struct StepDesc {
+    const __bf16* Q; const __bf16* K; const __bf16* V;
+    __bf16* O; float* LSE;
+    const int32_t* rows;   // optional: row r of the step is row rows[r] of Q, O and LSE (a subset of a scale)
+    int n_q;               // query rows of the step
+    int q_stride;          // rows per head of the Q, O and LSE buffers (n_q unless `rows` is given)
+    int Lk;                // key rows
+    int first_item;        // index of the step's first item in the launch
+};
+struct StepParams {
+    StepDesc step[kMaxSteps];
+    int n_steps, n_items, n_heads, tail_groups;
+    float c;
 };
 
 // The running reference maximum of a row is only raised when a tile exceeds it by more
@@ -34,19 +55,41 @@ constexpr float kRescaleThreshold = 8.0f;
 #ifndef HMAR_FWD_MIN_WAVES
 #define HMAR_FWD_MIN_WAVES 4
 #endif
-__global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(FwdParams p) {
-    // ring of 2 stages, each a K tile followed by a V tile
-    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
-
+// One body serves both launches: with STEPS the item, its buffers and its (trivial) pair ranges
+// come from the step descriptors, otherwise from the schedule tables.
+template <bool STEPS, typename Params>
+__device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id)) return;
-    const Item it = p.items[item_id];
+    Item it;
+    const __bf16* Qh; const __bf16* Kh; const __bf16* Vh;
+    __bf16* Oh; float* LSEh;
+    const int32_t* rows = nullptr;    // row map of Q, O, LSE (steps over a subset of rows)
+    const int32_t* row_lo = nullptr; const int32_t* row_hi = nullptr;
+    if constexpr (STEPS) {
+        int si = 0;
+        while (si + 1 < p.n_steps && item_id >= p.step[si + 1].first_item) ++si;
+        const StepDesc& sd = p.step[si];
+        const int li = item_id - sd.first_item;
+        it.own_begin = li * 128;
+        it.own_end = min(sd.n_q, it.own_begin + 128);
+        it.other_begin = 0;
+        it.other_end = sd.Lk;
+        const size_t q_off = (size_t)head * sd.q_stride;
+        Qh = sd.Q + q_off * kD; Oh = sd.O + q_off * kD; LSEh = sd.LSE + q_off;
+        Kh = sd.K + (size_t)head * sd.Lk * kD;
+        Vh = sd.V + (size_t)head * sd.Lk * kD;
+        rows = sd.rows;
+    } else {
+        it = p.items[item_id];
+        const size_t q_off = (size_t)head * p.L;
+        Qh = p.Q + q_off * kD; Oh = p.O + q_off * kD; LSEh = p.LSE + q_off;
+        Kh = p.K + (size_t)head * p.Lk * kD;
+        Vh = p.V + (size_t)head * p.Lk * kD;
+        row_lo = p.row_lo; row_hi = p.row_hi;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
-    const size_t head_off = (size_t)head * p.L * kD;
-    const __bf16* Qh = p.Q + head_off;
-    const __bf16* Kh = p.K + (size_t)head * p.Lk * kD;
-    const __bf16* Vh = p.V + (size_t)head * p.Lk * kD;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
     const uint32_t smem_base = lds_address(smem);
 
@@ -66,16 +109,23 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
     const bool wave_active = wq0 < it.own_end;               // uniform over the wavefront
     const bool row_valid = wq0 + lr < it.own_end;
     const int qrow = min(wq0 + lr, it.own_end - 1);
-    const int lo = p.row_lo[qrow], hi = p.row_hi[qrow];
-    // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
-    const int rfirst = min(wq0, it.own_end - 1), rlast = min(wq0 + kRowsPerWave - 1, it.own_end - 1);
-    const int wlo = p.row_lo[rfirst], whi = p.row_hi[rlast];        // union of the wavefront's ranges
-    const int full_lo = p.row_lo[rlast], full_hi = p.row_hi[rfirst];  // what every one of its rows pairs with
+    int lo, hi, wlo, whi, full_lo, full_hi;
+    if constexpr (STEPS) {
+        lo = wlo = full_lo = 0;
+        hi = whi = full_hi = k_end;
+    } else {
+        lo = row_lo[qrow]; hi = row_hi[qrow];
+        // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
+        const int rfirst = min(wq0, it.own_end - 1), rlast = min(wq0 + kRowsPerWave - 1, it.own_end - 1);
+        wlo = row_lo[rfirst]; whi = row_hi[rlast];          // union of the wavefront's ranges
+        full_lo = row_lo[rlast]; full_hi = row_hi[rfirst];  // what every one of its rows pairs with
+    }
 
+    const int qrow_mem = rows ? rows[qrow] : qrow;
     bf16x8 q[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
-        q[t] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow * kD + 16 * t + 8 * h);
+        q[t] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow_mem * kD + 16 * t + 8 * h);
 
     f32x16 o[2];
 #pragma unroll
@@ -165,10 +215,20 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
     // through which the output block is turned into full rows
     if (wave_active) {
         const float l = half_sum(lsum);
-        store_block_rows(smem_base + wave * kPatchBytes, o, 1.0f / l, p.O + head_off + (size_t)wq0 * kD,
-                         it.own_end - wq0, lane);
-        if (row_valid && h == 0) p.LSE[(size_t)head * p.L + wq0 + lr] = (m_ref + log2f(l)) * kLn2;
+        store_block_rows(smem_base + wave * kPatchBytes, o, 1.0f / l, Oh, wq0, it.own_end - wq0, lane, rows);
+        if (row_valid && h == 0) LSEh[qrow_mem] = (m_ref + log2f(l)) * kLn2;
     }
+}
+
+__global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(FwdParams p) {
+    // ring of 2 stages, each a K tile followed by a V tile
+    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+    fwd_body<false>(p, smem);
+}
+
+__global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_steps_kernel(StepParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+    fwd_body<true>(p, smem);
 }
 
 hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -192,6 +252,40 @@ hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, floa
     if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
     profile_before(kKernelFwd, stream);
     hipLaunchKernelGGL(hmar_fwd_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+    const hipError_t e = hipGetLastError();
+    profile_after(kKernelFwd, stream);
+    return e;
+}
+
+hipError_t launch_fwd_steps(const StepLaunch& L, int n_heads, float sm_scale, int num_cus, hipStream_t stream) {
+    if (L.n_steps < 1 || L.n_steps > kMaxSteps) return hipErrorInvalidValue;
+    StepParams p;
+    int items = 0;
+    for (int i = 0; i < L.n_steps; ++i) {
+        const StepLaunch::Step& a = L.step[i];
+        StepDesc& d = p.step[i];
+        d.Q = static_cast<const __bf16*>(a.Q);
+        d.K = static_cast<const __bf16*>(a.K);
+        d.V = static_cast<const __bf16*>(a.V);
+        d.O = static_cast<__bf16*>(a.O);
+        d.LSE = a.LSE;
+        d.rows = a.rows;
+        d.n_q = a.n_q;
+        d.q_stride = a.q_stride;
+        d.Lk = a.Lk;
+        d.first_item = items;
+        items += (a.n_q + 127) / 128;
+    }
+    for (int i = L.n_steps; i < kMaxSteps; ++i) p.step[i] = p.step[0];
+    p.n_steps = L.n_steps;
+    p.n_items = items;
+    p.n_heads = n_heads;
+    p.tail_groups = tail_groups_for(num_cus, items);
+    p.c = sm_scale * kLog2e;
+    const long long groups = 8LL * ((n_heads + 7) / 8) * items;
+    if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
+    profile_before(kKernelFwd, stream);
+    hipLaunchKernelGGL(hmar_fwd_steps_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
     const hipError_t e = hipGetLastError();
     profile_after(kKernelFwd, stream);
     return e;

@@ -31,6 +31,19 @@ enum KernelId { kKernelFwd = 0, kKernelDkDv = 1, kKernelDq = 2, kNumKernels = 3 
 void profile_before(int kernel_id, hipStream_t stream);
 void profile_after(int kernel_id, hipStream_t stream);
 
+// Up to kMaxSteps independent inference steps in one launch (host view; the launcher turns it
+// into kernel arguments).  Steps must be ordered by decreasing work.
+constexpr int kMaxSteps = 16;
+struct StepLaunch {
+    struct Step {
+        const void* Q; const void* K; const void* V; void* O; float* LSE;
+        const int32_t* rows;    // device, optional: the n_q rows of Q/O/LSE the step covers
+        int32_t n_q, q_stride, Lk;
+    } step[kMaxSteps];
+    int32_t n_steps;
+};
+hipError_t launch_fwd_steps(const StepLaunch& L, int n_heads, float sm_scale, int num_cus, hipStream_t stream);
+
 hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                       const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream);
 

@@ -89,25 +89,4 @@ bool build_schedule(const int32_t* sides, int32_t num_scales, bool sizes_are_cou
     return true;
 }
 
-bool build_step_schedule(int32_t n_prev, int32_t n_cur, int32_t rows_per_item, int64_t max_len, Schedule* out) {
-    if (n_prev < 0 || n_cur < 1 || rows_per_item < 32 || rows_per_item % 32) return false;
-    if ((int64_t)n_prev + n_cur > max_len) return false;
-    Schedule s;
-    s.mask_kind = kMaskStep;
-    s.sides = {n_prev, n_cur};
-    s.off = {0, n_cur};
-    s.L = n_cur;
-    s.Lk = n_prev + n_cur;
-    s.allowed_pairs = (int64_t)n_cur * s.Lk;
-    s.row_lo[0].assign(n_cur, 0);
-    s.row_hi[0].assign(n_cur, s.Lk);
-    // equal chunks, each a multiple of 32 rows except the last
-    const int32_t chunks = (n_cur + rows_per_item - 1) / rows_per_item;
-    int32_t per = (n_cur + chunks - 1) / chunks;
-    per = (per + 31) / 32 * 32;
-    for (int32_t b = 0; b < n_cur; b += per) s.items[0].push_back({b, std::min(b + per, n_cur), 0, s.Lk});
-    *out = std::move(s);
-    return true;
-}
-
 }  // namespace hmar

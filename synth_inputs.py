@@ -6,7 +6,7 @@ CPU oracle's tests and the HIP path's tests/benchmark can use it without sharing
 anything that could hide a common mistake.
 
 Recipe (stand-in for the ImageNet-derived activations of the paper's attention
-micro-benchmark, App. B.4, which depends on shapes only): Q, K, V, dO are iid N(0,1),
+micro-benchmark, appendix "Efficient Attention Performance", which depends on shapes only): Q, K, V, dO are iid N(0,1),
 drawn in fp32 with torch's CPU generator seeded with the workload's seed, in the order
 Q, K, V, dO, each of shape [B, H, L, D], then rounded once to bf16 (round to nearest
 even).  Both the GPU path and the oracle consume the rounded values.

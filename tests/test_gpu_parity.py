@@ -56,6 +56,14 @@ def _gpu_run(Q, K, V, dO, sides, sm_scale, backward=True):
     return res
 
 
+OBSERVED = {}      # label -> {tensor: largest absolute error seen}; written out at the end of the session
+
+
+def _note(label, name, value):
+    d = OBSERVED.setdefault(label, {})
+    d[name] = max(d.get(name, 0.0), float(value))
+
+
 def _compare(res, ref, heads, label, grad_bounds=None):
     for name in ("O", "dQ", "dK", "dV"):
         if name not in res or name not in ref:
@@ -63,13 +71,39 @@ def _compare(res, ref, heads, label, grad_bounds=None):
         got = np.stack([si.to_f64(res[name][b, h]) for (b, h) in heads])
         assert np.isfinite(got).all(), (label, name, "non-finite")
         err = np.abs(got - ref[name])
+        _note(label, name, err.max())
         if grad_bounds is not None and name in grad_bounds:
+            _note(label, name + " / its derived bound", (err / grad_bounds[name]).max())
             assert (err <= grad_bounds[name]).all(), (label, name, float((err - grad_bounds[name]).max()))
         else:
             assert err.max() <= TOL_ABS, (label, name, float(err.max()))
     got = np.stack([si.to_f64(res["LSE"][b, h]) for (b, h) in heads])
     bound = TOL_LSE_REL * np.maximum(1.0, np.abs(ref["LSE"]))
+    _note(label, "LSE / its bound", (np.abs(got - ref["LSE"]) / bound).max())
     assert (np.abs(got - ref["LSE"]) <= bound).all(), (label, "LSE", float(np.abs(got - ref["LSE"]).max()))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _write_observed_errors():
+    """After the module's tests: the largest errors seen per case, for the record the design
+    notes quote (printed, and saved next to the other outputs of a GPU run when that folder exists)."""
+    yield
+    import json
+    import os
+    text = json.dumps(OBSERVED, indent=1, sort_keys=True)
+    print("\nobserved maximum errors against the oracle:\n" + text)
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "observed_errors.json"), "w") as f:
+            f.write(text + "\n")
+
+
+def _nan_like(t):
+    return torch.full_like(t, float("nan"))
+
+
+def _nan_stats(shape, device):
+    return torch.full(shape, float("nan"), dtype=torch.float32, device=device)
 
 
 def _operand_rounding_bounds(Q, K, V, dO, sides, sm_scale, heads, ref):
@@ -152,20 +186,45 @@ def test_long_scales_and_head_counts_off_the_xcd_grid(sides, B, H):
     _compare(res, _oracle_heads(Q, K, V, dO, sides, 1.0 / math.sqrt(D), heads), heads, f"{sides} B{B} H{H}")
 
 
-@pytest.mark.parametrize("name,n_heads", [("256px_b16_h16", 10), ("256px_b32_h24", 8), ("256px_b32_h30", 4),
-                                          ("512px_b8_h24", 3)])
-def test_full_size_workloads_on_sampled_heads(name, n_heads):
-    # full problem size in the launch configuration the benchmark times; the oracle is
-    # evaluated on a seeded sample of (b, h) slices, each compared in full
+@pytest.mark.parametrize("name", ["256px_b16_h16", "256px_b32_h24", "256px_b32_h30", "512px_b8_h24"])
+def test_full_size_workloads_every_head(name):
+    # Full problem size in the launch configuration the benchmark times; every (b, h) slice is
+    # compared element by element with the oracle (a few seconds of CPU work per workload), in
+    # chunks of heads so that the fp64 references stay small.
+    # Bar: the flat 2e-2.  Over tens of millions of gradient elements a handful land above it,
+    # in rows whose softmax is peaked on one key: there Delta_i = sum_d dO_id O_id, formed from
+    # the forward's bf16 output as the interface prescribes, is off by up to 2^-9 sum_d |dO O|,
+    # which moves dS_ij by P_ij times that.  Such elements (counted and recorded) must lie within
+    # the element-wise bound that this rounding implies; everything else within 2e-2.
     w = si.WORKLOADS[name]
     Q, K, V, dO = si.make_inputs(w)
     sm = 1.0 / math.sqrt(w.D)
     res = _gpu_run(Q, K, V, dO, w.sides, sm)
-    heads = _sample_heads(w.B, w.H, n_heads, seed=w.seed)
-    _compare(res, _oracle_heads(Q, K, V, dO, w.sides, sm, heads), heads, name)
-    # properties that hold at any size, over every head
-    for t in res.values():
-        assert torch.isfinite(t.float()).all()
+    res = {k: t.cpu() for k, t in res.items()}
+    heads = _all_heads(w.B, w.H)
+    above = {"dQ": 0, "dK": 0, "dV": 0}
+    for c in range(0, len(heads), 32):
+        chunk = heads[c:c + 32]
+        ref = _oracle_heads(Q, K, V, dO, w.sides, sm, chunk)
+        hot = []
+        for n, (b, h) in enumerate(chunk):
+            for t in above:
+                k_over = int((np.abs(si.to_f64(res[t][b, h]) - ref[t][n]) > TOL_ABS).sum())
+                above[t] += k_over
+                if k_over and (b, h) not in hot:
+                    hot.append((b, h))
+        calm = [bh for bh in chunk if bh not in hot]
+        pick = lambda hs: {t: x[[chunk.index(bh) for bh in hs]] for t, x in ref.items()}
+        if calm:
+            _compare(res, pick(calm), calm, name)
+        if hot:
+            r = pick(hot)
+            bounds = _operand_rounding_bounds(Q, K, V, dO, w.sides, sm, hot, r)
+            bounds = {t: np.maximum(x, TOL_ABS) for t, x in bounds.items()}
+            _compare(res, r, hot, name + " (heads with elements above 2e-2)", grad_bounds=bounds)
+    for t, k_over in above.items():
+        _note(name, f"{t}: elements above 2e-2 (of {w.B * w.H * w.L * w.D})", k_over)
+        assert k_over <= 1e-6 * w.B * w.H * w.L * w.D, (name, t, k_over)
     # scale 1 has one token that sees only itself: O[...,0,:] == V[...,0,:] exactly
     assert torch.equal(res["O"][:, :, 0, :].cpu(), V[:, :, 0, :])
 
@@ -362,15 +421,17 @@ def test_hip_graph_replays_match_eager_launches():
 
 @pytest.mark.parametrize("sides", [si.SIDES_TINY, (2, 5), (3, 1, 4, 1, 5), (6, 7, 8, 9, 10), si.SIDES_256])
 def test_block_causal_mask_variant(sides):
-    # VAR's block-causal mask (Sec. 2) through the same kernels; oracle = dense attention
+    # VAR's block-causal mask (Sec. "Background") through the same kernels; oracle = dense attention
     # under the explicit block-causal mask and its analytic backward
     L = sum(s * s for s in sides)
     B, H, D = 1, 3, 64
     Q, K, V, dO = si.draw((B, H, L, D), seed=200 + L, n_tensors=4)
     d = _dev()
     q, k, v, g = (t.to(d) for t in (Q, K, V, dO))
-    O, LSE = hm.hmar_attn_fwd_masked(q, k, v, sides, hm.HMAR_MASK_BLOCK_CAUSAL)
-    dQ, dK, dV = hm.hmar_attn_bwd_masked(q, k, v, O, g, LSE, sides, hm.HMAR_MASK_BLOCK_CAUSAL)
+    O, LSE = hm.hmar_attn_fwd_masked(q, k, v, sides, hm.HMAR_MASK_BLOCK_CAUSAL, O=_nan_like(q),
+                                     LSE=_nan_stats(q.shape[:3], d))
+    dQ, dK, dV = hm.hmar_attn_bwd_masked(q, k, v, O, g, LSE, sides, hm.HMAR_MASK_BLOCK_CAUSAL,
+                                         dQ=_nan_like(q), dK=_nan_like(q), dV=_nan_like(q))
     torch.cuda.synchronize()
     mask = orc.block_causal_mask(sides)
     ref = {n: [] for n in ("O", "LSE", "dQ", "dK", "dV")}
@@ -393,7 +454,7 @@ def test_block_causal_mask_variant(sides):
                          ids=lambda c: "x".join(map(str, c)))
 @pytest.mark.parametrize("kind", ["markov", "block_causal"])
 def test_scales_given_as_token_counts(counts, kind):
-    # scales as H_k x W_k token maps that need not be square (Sec. 2): the sizes are token
+    # scales as H_k x W_k token maps that need not be square (Sec. "Background"): the sizes are token
     # counts; the last schedule is 1x1, 1x2, 2x3, ... , 12x13, 15x16
     L = sum(counts)
     B, H, D = 1, 3, 64
@@ -404,8 +465,9 @@ def test_scales_given_as_token_counts(counts, kind):
         flag, mask = hm.HMAR_MASK_MARKOV | hm.HMAR_SCALE_COUNTS, orc.markov_mask_from_counts(counts)
     else:
         flag, mask = hm.HMAR_MASK_BLOCK_CAUSAL | hm.HMAR_SCALE_COUNTS, orc.block_causal_mask_from_counts(counts)
-    O, LSE = hm.hmar_attn_fwd_masked(q, k, v, counts, flag)
-    dQ, dK, dV = hm.hmar_attn_bwd_masked(q, k, v, O, g, LSE, counts, flag)
+    O, LSE = hm.hmar_attn_fwd_masked(q, k, v, counts, flag, O=_nan_like(q), LSE=_nan_stats(q.shape[:3], d))
+    dQ, dK, dV = hm.hmar_attn_bwd_masked(q, k, v, O, g, LSE, counts, flag,
+                                         dQ=_nan_like(q), dK=_nan_like(q), dV=_nan_like(q))
     torch.cuda.synchronize()
     ref = {n: [] for n in ("O", "LSE", "dQ", "dK", "dV")}
     for hh in range(H):
@@ -435,16 +497,106 @@ def test_counts_of_square_scales_give_the_same_bits_as_side_lengths():
 
 @pytest.mark.parametrize("n_prev,n_cur", [(0, 1), (1, 4), (25, 36), (100, 169), (169, 256), (7, 130), (300, 33)])
 def test_inference_step_forward(n_prev, n_cur):
-    # one KV-cache-free step (Sec. 3.1): n_cur queries against the predecessor block + themselves
+    # one KV-cache-free step (Sec. "Efficient Markovian Next-Scale Prediction"): n_cur queries
+    # against the predecessor block + themselves
     B, H, D = 2, 3, 64
     Q = si.draw((B, H, n_cur, D), seed=300 + n_cur, n_tensors=1)[0]
     K, V = si.draw((B, H, n_prev + n_cur, D), seed=400 + n_prev, n_tensors=2)
     d = _dev()
-    O, LSE = hm.hmar_attn_step_fwd(Q.to(d), K.to(d), V.to(d), n_prev)
+    q = Q.to(d)
+    O, LSE = hm.hmar_attn_step_fwd(q, K.to(d), V.to(d), n_prev, O=_nan_like(q), LSE=_nan_stats((B, H, n_cur), d))
     torch.cuda.synchronize()
     rO, rLSE = orc.attn_step_fwd(si.to_f64(Q), si.to_f64(K), si.to_f64(V), n_prev)
-    assert np.abs(si.to_f64(O) - rO).max() <= TOL_ABS
-    assert (np.abs(si.to_f64(LSE) - rLSE) <= TOL_LSE_REL * np.maximum(1.0, np.abs(rLSE))).all()
+    _compare(dict(O=O, LSE=LSE), dict(O=rO.reshape(B * H, n_cur, D), LSE=rLSE.reshape(B * H, n_cur)),
+             _all_heads(B, H), "inference step")
+
+
+def _step_shapes_256px():
+    counts = [s * s for s in si.SIDES_256]
+    return [(counts[k - 1] if k else 0, counts[k]) for k in range(len(counts))]
+
+
+def test_all_steps_of_a_schedule_in_one_call_at_the_serving_batch():
+    # the ten steps of the 256px schedule at B = 64, H = 24 (1536 heads, 192 head groups), issued
+    # as ONE call: every output starts as NaN and must come back finite; a seeded sample of
+    # heads is compared with the oracle step by step, and the batched call must give the bits
+    # of ten single-step calls
+    B, H, D = 64, 24, 64
+    d = _dev()
+    shapes = _step_shapes_256px()
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    Qs, Ks, Vs = [], [], []
+    for (n_prev, n_cur) in shapes:
+        Qs.append(torch.randn((B, H, n_cur, D), generator=g).to(torch.bfloat16))
+        Ks.append(torch.randn((B, H, n_prev + n_cur, D), generator=g).to(torch.bfloat16))
+        Vs.append(torch.randn((B, H, n_prev + n_cur, D), generator=g).to(torch.bfloat16))
+    q, k, v = ([t.to(d) for t in ts] for ts in (Qs, Ks, Vs))
+    n_prevs = [a for a, _ in shapes]
+    Os, LSEs = hm.hmar_attn_steps_fwd(q, k, v, n_prevs, Os=[_nan_like(t) for t in q],
+                                      LSEs=[_nan_stats(t.shape[:3], d) for t in q])
+    torch.cuda.synchronize()
+    heads = _sample_heads(B, H, 12, seed=5)
+    for i, (n_prev, n_cur) in enumerate(shapes):
+        assert torch.isfinite(Os[i].float()).all() and torch.isfinite(LSEs[i]).all(), shapes[i]
+        O1, L1 = hm.hmar_attn_step_fwd(q[i], k[i], v[i], n_prev)
+        torch.cuda.synchronize()
+        assert torch.equal(O1, Os[i]) and torch.equal(L1, LSEs[i]), shapes[i]
+        ref = {"O": [], "LSE": []}
+        for (b, h) in heads:
+            rO, rL = orc.attn_step_fwd(si.to_f64(Qs[i][b, h])[None, None], si.to_f64(Ks[i][b, h])[None, None],
+                                       si.to_f64(Vs[i][b, h])[None, None], n_prev)
+            ref["O"].append(rO[0, 0]); ref["LSE"].append(rL[0, 0])
+        _compare(dict(O=Os[i], LSE=LSEs[i]), {n: np.stack(x) for n, x in ref.items()}, heads, "steps at B64 H24")
+
+
+def test_more_steps_than_one_launch_holds():
+    # 40 steps (more than the 16 a launch carries) of mixed sizes, each against the oracle
+    B, H, D = 1, 5, 64
+    d = _dev()
+    rng = np.random.default_rng(3)
+    shapes = [(int(rng.integers(0, 70)), int(rng.integers(1, 150))) for _ in range(40)]
+    Qs = [si.draw((B, H, c, D), seed=900 + i, n_tensors=1)[0] for i, (p, c) in enumerate(shapes)]
+    KVs = [si.draw((B, H, p + c, D), seed=950 + i, n_tensors=2) for i, (p, c) in enumerate(shapes)]
+    q = [t.to(d) for t in Qs]
+    Os, LSEs = hm.hmar_attn_steps_fwd(q, [kv[0].to(d) for kv in KVs], [kv[1].to(d) for kv in KVs],
+                                      [p for p, _ in shapes], Os=[_nan_like(t) for t in q],
+                                      LSEs=[_nan_stats(t.shape[:3], d) for t in q])
+    torch.cuda.synchronize()
+    for i, (p, c) in enumerate(shapes):
+        rO, rL = orc.attn_step_fwd(si.to_f64(Qs[i]), si.to_f64(KVs[i][0]), si.to_f64(KVs[i][1]), p)
+        _compare(dict(O=Os[i], LSE=LSEs[i]), dict(O=rO.reshape(B * H, c, D), LSE=rL.reshape(B * H, c)),
+                 _all_heads(B, H), "forty steps")
+
+
+@pytest.mark.parametrize("n_prev,n_cur,n_rows", [(169, 256, 97), (100, 169, 169), (25, 36, 1), (0, 300, 131), (64, 100, 32)])
+def test_refinement_pass_over_a_subset_of_rows(n_prev, n_cur, n_rows):
+    # masked refinement inside a scale (Sec. "Hierarchical Multi-Step Masked Generation", Eq. 6):
+    # only the listed (re-masked) query rows are predicted again.  Oracle: those rows of the
+    # full step; every other row of O and LSE must keep the sentinel it held before the call
+    B, H, D = 2, 9, 64
+    Q = si.draw((B, H, n_cur, D), seed=500 + n_cur, n_tensors=1)[0]
+    K, V = si.draw((B, H, n_prev + n_cur, D), seed=600 + n_prev, n_tensors=2)
+    rows = np.sort(np.random.default_rng(n_rows).choice(n_cur, size=n_rows, replace=False)).astype(np.int32)
+    if n_rows > 1:
+        rows = rows[::-1].copy()            # any order is allowed
+    d = _dev()
+    q = Q.to(d)
+    O = torch.full_like(q, 7.0)
+    LSE = torch.full((B, H, n_cur), -3.0, dtype=torch.float32, device=d)
+    hm.hmar_attn_step_fwd_rows(q, K.to(d), V.to(d), n_prev, torch.from_numpy(rows).to(d), O, LSE)
+    torch.cuda.synchronize()
+    rO, rLSE = orc.attn_step_fwd(si.to_f64(Q), si.to_f64(K), si.to_f64(V), n_prev)
+    got_O, got_L = si.to_f64(O), si.to_f64(LSE)
+    other = np.setdiff1d(np.arange(n_cur), rows)
+    assert (got_O[:, :, other] == 7.0).all() and (got_L[:, :, other] == -3.0).all()
+    err = np.abs(got_O[:, :, rows] - rO[:, :, rows])
+    _note("refinement rows", "O", err.max())
+    assert err.max() <= TOL_ABS
+    lref = rLSE[:, :, rows]
+    assert (np.abs(got_L[:, :, rows] - lref) <= TOL_LSE_REL * np.maximum(1.0, np.abs(lref))).all()
+    # the full step over all rows gives the same bits on the listed rows when they form whole
+    # blocks in order; in general only the oracle bar holds, which is what is asserted above
 
 
 def test_inference_steps_reproduce_the_training_forward():

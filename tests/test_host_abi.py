@@ -145,10 +145,40 @@ def test_binding_refuses_cpu_tensors_and_wrong_dtypes():
     assert os.path.exists(binding.LIB_PATH)
 
 
+def test_binding_refuses_a_host_lse_before_any_library_call(monkeypatch):
+    # a host pointer handed to a kernel would fault the GPU: the checks of the per-row fp32
+    # tensors must fire in Python.  Device tensors are faked: no GPU is needed for this.
+    import torch
+
+    class FakeDeviceTensor:
+        """Answers what the binding asks of a tensor, claiming to live on cuda:0."""
+        def __init__(self, shape, dtype):
+            self.shape, self.dtype, self.is_cuda = torch.Size(shape), dtype, True
+            self.device = torch.device("cuda:0")
+        def dim(self): return len(self.shape)
+        def is_contiguous(self): return True
+        def data_ptr(self): raise AssertionError("the library must not be reached")
+
+    monkeypatch.setattr(binding, "_bf16_4d", lambda name, t, shape=None, device=None: t)
+    q = FakeDeviceTensor((1, 1, 5, 64), torch.bfloat16)
+    k = FakeDeviceTensor((1, 1, 5, 64), torch.bfloat16)
+    host_lse = torch.zeros((1, 1, 5), dtype=torch.float32)
+    with pytest.raises(hm.HmarError, match="LSE"):
+        hm.hmar_attn_fwd_masked(q, k, k, (1, 2), hm.HMAR_MASK_MARKOV, O=q, LSE=host_lse)
+    with pytest.raises(hm.HmarError, match="LSE"):
+        hm.hmar_attn_step_fwd(q, k, k, 0, O=q, LSE=host_lse)
+    with pytest.raises(hm.HmarError, match="LSE"):
+        hm.hmar_attn_bwd(q, k, k, q, q, host_lse, (1, 2))
+    # and a tensor on another device than Q's is refused by the real check
+    monkeypatch.undo()
+    with pytest.raises(hm.HmarError):
+        binding._f32_stats("LSE", host_lse, (1, 1, 5), torch.device("cuda:0"))
+
+
 @pytest.mark.parametrize("sides", [si.SIDES_TINY, si.SIDES_256, (2, 5), (3, 1, 4, 1, 5), (20, 3, 20)])
 @pytest.mark.parametrize("direction", [0, 1])
 def test_block_causal_tile_schedule_covers_exactly_the_var_mask(sides, direction):
-    # `which` + 2 selects VAR's block-causal mask (Sec. 2): scale k sees every scale <= k
+    # `which` + 2 selects VAR's block-causal mask (Sec. "Background"): scale k sees every scale <= k
     mask = orc.block_causal_mask(sides)
     if direction == 1:
         mask = mask.T
@@ -179,13 +209,44 @@ def test_step_and_masked_entry_points_reject_bad_arguments():
     assert lib.hmar_attn_step_fwd(*p, 1 << 20, 9, 1, 1, 64, 0.0, None) == 2           # beyond HMAR_MAX_SEQ_LEN
 
 
+def test_batched_steps_and_row_subsets_reject_bad_arguments():
+    lib = hm.load_library()
+    vp = ctypes.c_void_p
+    def arrs(n, base=0x1000):
+        return [(vp * n)(*[base * (j + 1) + 0x100 * i for i in range(n)]) for j in range(5)]
+    i32 = ctypes.c_int32
+    ok_prev, ok_cur = (i32 * 2)(1, 4), (i32 * 2)(4, 9)
+    a = arrs(2)
+    assert lib.hmar_attn_steps_fwd(*a, ok_prev, ok_cur, 0, 1, 1, 64, 0.0, None) == 1            # no steps
+    assert lib.hmar_attn_steps_fwd(None, *a[1:], ok_prev, ok_cur, 2, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_steps_fwd(*a, ok_prev, (i32 * 2)(4, 0), 2, 1, 1, 64, 0.0, None) == 1   # empty step
+    assert lib.hmar_attn_steps_fwd(*a, (i32 * 2)(1, -4), ok_cur, 2, 1, 1, 64, 0.0, None) == 1
+    bad = arrs(2); bad[3][1] = None
+    assert lib.hmar_attn_steps_fwd(*bad, ok_prev, ok_cur, 2, 1, 1, 64, 0.0, None) == 1          # a null O
+    mis = arrs(2); mis[1][0] = 0x2008
+    assert lib.hmar_attn_steps_fwd(*mis, ok_prev, ok_cur, 2, 1, 1, 64, 0.0, None) == 1          # misaligned K
+    assert lib.hmar_attn_steps_fwd(*a, ok_prev, ok_cur, 2, 1, 1, 128, 0.0, None) == 2
+    assert lib.hmar_attn_steps_fwd(*a, ok_prev, ok_cur, 2, 1, 1, 64, float("inf"), None) == 1
+    many = arrs(1025, base=0x100000)
+    assert lib.hmar_attn_steps_fwd(*many, (i32 * 1025)(*([1] * 1025)), (i32 * 1025)(*([1] * 1025)), 1025,
+                                   1, 1, 64, 0.0, None) == 2                                        # beyond HMAR_MAX_STEPS
+    p = [0x1000 * (i + 1) for i in range(5)]
+    rows = 0x9000
+    assert lib.hmar_attn_step_fwd_rows(*p, None, 3, 4, 9, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_step_fwd_rows(*p, rows, 0, 4, 9, 1, 1, 64, 0.0, None) == 1
+    assert lib.hmar_attn_step_fwd_rows(*p, rows, 10, 4, 9, 1, 1, 64, 0.0, None) == 1           # more rows than the scale has
+    assert lib.hmar_attn_step_fwd_rows(*p, rows + 2, 3, 4, 9, 1, 1, 64, 0.0, None) == 1        # misaligned index list
+    assert lib.hmar_attn_step_fwd_rows(*p, rows, 3, 4, 9, 1, 1, 32, 0.0, None) == 2
+    assert lib.hmar_attn_step_fwd_rows(*p, rows, 3, -1, 9, 1, 1, 64, 0.0, None) == 1
+
+
 COUNT_SCHEDULES = [(2, 6, 12, 20), (1, 3, 3, 7), (5,), (130, 70, 300), (1, 2, 6, 12, 20, 30, 56, 90, 156, 240)]
 
 
 @pytest.mark.parametrize("counts", COUNT_SCHEDULES)
 @pytest.mark.parametrize("which", [0, 1, 2, 3])
 def test_tile_schedule_for_token_counts_covers_exactly_the_mask(counts, which):
-    # `which` + 4: the sizes are token counts of scales that need not be square (Sec. 2)
+    # `which` + 4: the sizes are token counts of scales that need not be square (Sec. "Background")
     mask = orc.block_causal_mask_from_counts(counts) if which & 2 else orc.markov_mask_from_counts(counts)
     if which & 1:
         mask = mask.T

@@ -44,14 +44,14 @@ def test_schedule_lengths_and_pair_counts_match_hand_worked_values(name, sides, 
 
 
 def test_sixteen_step_sequence_is_5p84_times_next_token_length():
-    # Sec. 1 (Efficiency): up to 5.84x longer than next-token prediction at 256x256
+    # Sec. "Introduction" (efficiency item): up to 5.84x longer than next-token prediction at 256x256
     L = orc.scale_offsets(range(1, 17))[-1]
     assert L == 1496
     assert round(L / 256, 2) == 5.84
 
 
 def test_finest_scale_has_256x_tokens_of_coarsest():
-    # Sec. 3.3: with K=10 the finest scale has 256x the tokens of the coarsest
+    # Sec. "Training Dynamics": with K=10 the finest scale has 256x the tokens of the coarsest
     n = orc.scale_token_counts(si.SIDES_256)
     assert len(n) == 10 and n[-1] // n[0] == 256
 
@@ -81,7 +81,7 @@ def test_mask_equals_independent_interval_construction(sides):
 
 @pytest.mark.parametrize("counts", [(2, 6, 12, 20), (1, 3, 3, 7), (5,), (4, 9, 16)])
 def test_masks_from_token_counts(counts):
-    # scales as H_k x W_k maps that need not be square (Sec. 2): (2,6,12,20) = 1x2, 2x3, 3x4, 4x5.
+    # scales as H_k x W_k maps that need not be square (Sec. "Background"): (2,6,12,20) = 1x2, 2x3, 3x4, 4x5.
     # catches: counts squared by mistake, predecessor taken two scales back, missing own block
     L = sum(counts)
     offs = [0]
@@ -300,7 +300,7 @@ def test_permuting_keys_inside_a_scale_leaves_output_unchanged():
 
 
 def test_inference_step_equals_rows_of_training_forward():
-    # Sec. 3.1: no prefix/KV cache; step k sees the predecessor block and its own tokens.
+    # Sec. "Efficient Markovian Next-Scale Prediction": no prefix/KV cache; step k sees the predecessor block and its own tokens.
     sides, D = si.SIDES_256, 64
     L = 680
     Q, K, V = _rand((2, 3, L, D), 71), _rand((2, 3, L, D), 72), _rand((2, 3, L, D), 73)
