@@ -25,7 +25,7 @@
  *    with the same sizes costs one look-up).  That first use allocates and copies
  *    synchronously: make it outside a HIP stream capture; later calls with the same schedule
  *    only launch kernels and may be captured into a graph.  The inference-step entry points
- *    (hmar_attn_step*) never allocate.
+ *    (hmar_attn_step*) never allocate, nor does hmar_attn_bwd_noalloc.
  *  - Errors are return codes.  Argument checks happen before any device work.
  *  - Inputs must be finite.  Rounding: products accumulate in fp32; the softmax
  *    probabilities (and, in the backward, dS) are rounded to bf16 before the second
@@ -155,6 +155,25 @@ hmar_status hmar_attn_bwd_masked(const void* Q, const void* K, const void* V, co
                                  const int32_t* side_lens, int32_t num_scales, int32_t mask_kind,
                                  int32_t B, int32_t H, int32_t D, float sm_scale,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* hmar_attn_bwd for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments without the workspace, same results bit for bit.  The two fp32 [B,H,L] arrays and
+ * the schedule tables live in a fixed array in the library's device image (about 8.2 MiB on
+ * every GPU the library runs on, held until the process ends); the call makes no hipMalloc,
+ * hipFree, memcpy or other allocating call: it only launches kernels.  Limits, beyond those of hmar_attn_bwd:
+ *   B*H*L <= HMAR_NOALLOC_MAX_ROWS and L <= HMAR_NOALLOC_MAX_SEQ_LEN, else HMAR_ERR_UNSUPPORTED.
+ * Every call on a GPU uses that GPU's one array, which keeps the last call's contents: calls
+ * that overlap in time on one GPU (two streams, two threads) race; calls on one stream, or
+ * ordered by events, are safe.  When the schedule differs from the previous call's on that GPU
+ * its tables (a few KB) are first written to the array by small kernels on `stream`, their
+ * contents carried in the kernel arguments.  Markovian mask, scales given by side lengths. */
+#define HMAR_NOALLOC_MAX_ROWS (1 << 20)
+#define HMAR_NOALLOC_MAX_SEQ_LEN 8192
+hmar_status hmar_attn_bwd_noalloc(const void* Q, const void* K, const void* V, const void* O,
+                                  const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+                                  const int32_t* side_lens, int32_t num_scales,
+                                  int32_t B, int32_t H, int32_t D, float sm_scale, void* stream);
 
 /* Host-only description of a schedule (no device work): prefix sums off[0..num_scales]
  * of side^2 and the number of unmasked (query, key) pairs per head.  Either output

@@ -58,6 +58,8 @@ def load_library() -> ctypes.CDLL:
     lib.hmar_attn_bwd_workspace_bytes_masked.argtypes = [pi32, i32, i32, i32, i32, i32]
     lib.hmar_attn_bwd.restype = ctypes.c_int
     lib.hmar_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, f32, vp, sz, vp]
+    lib.hmar_attn_bwd_noalloc.restype = ctypes.c_int
+    lib.hmar_attn_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, pi32, i32, i32, i32, i32, f32, vp]
     lib.hmar_schedule_describe.restype = ctypes.c_int
     lib.hmar_schedule_describe.argtypes = [pi32, i32, pi32, ctypes.POINTER(i64)]
     lib.hmar_schedule_tiles.restype = ctypes.c_int
@@ -312,6 +314,26 @@ def hmar_attn_bwd_masked(Q, K, V, O, dO, LSE, side_lens, mask_kind: int, sm_scal
                                         arr, n, int(mask_kind), B, H, D, float(sm_scale), workspace.data_ptr(),
                                         ws_bytes, _stream_handle(Q))
     _check(code, "hmar_attn_bwd_masked")
+    return dQ, dK, dV
+
+
+def hmar_attn_bwd_noalloc(Q, K, V, O, dO, LSE, side_lens, dQ, dK, dV, sm_scale: float = 0.0):
+    """The backward without a workspace and without any allocation (not even of outputs: the
+    caller passes dQ, dK, dV).  Markovian mask.  Returns (dQ, dK, dV)."""
+    lib = load_library()
+    _bf16_4d("Q", Q)
+    B, H, L, D = Q.shape
+    for name, t in (("K", K), ("V", V), ("O", O), ("dO", dO), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+        _bf16_4d(name, t, Q.shape, Q.device)
+    _f32_stats("LSE", LSE, (B, H, L), Q.device)
+    arr, n, L_sched = _sides_array(side_lens)
+    if L_sched != L:
+        raise HmarError("sequence length does not match the scale schedule")
+    with _on_device(Q.device):
+        code = lib.hmar_attn_bwd_noalloc(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+                                         LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                         arr, n, B, H, D, float(sm_scale), _stream_handle(Q))
+    _check(code, "hmar_attn_bwd_noalloc")
     return dQ, dK, dV
 
 

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libhmar_attn.so")
 
-SOURCES = ["api.cpp", "schedule.cpp", "fwd.hip", "bwd.hip"]
+SOURCES = ["api.cpp", "schedule.cpp", "fwd.hip", "bwd.hip", "no_alloc.hip"]
 
 # -packed-fp32-ops off: hipcc must not form v_pk_*_f32 from the fp32 softmax arithmetic.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

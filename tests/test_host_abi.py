@@ -240,6 +240,21 @@ def test_batched_steps_and_row_subsets_reject_bad_arguments():
     assert lib.hmar_attn_step_fwd_rows(*p, rows, 3, -1, 9, 1, 1, 64, 0.0, None) == 1
 
 
+def test_no_alloc_backward_rejects_what_the_fixed_array_cannot_hold():
+    lib = hm.load_library()
+    p = [0x1000 * (i + 1) for i in range(9)]
+    def call(sides, B, H, D=64):
+        arr = (ctypes.c_int32 * len(sides))(*sides)
+        return lib.hmar_attn_bwd_noalloc(*p, arr, len(sides), B, H, D, 0.0, None)
+    assert call((91,), 1, 1) == 2                    # L = 8281 beyond HMAR_NOALLOC_MAX_SEQ_LEN
+    assert call(si.SIDES_256, 64, 25) == 2           # 1 088 000 rows beyond HMAR_NOALLOC_MAX_ROWS
+    assert call(si.SIDES_256, 1, 1, D=128) == 2
+    assert call((1, 0), 1, 1) == 1
+    q = list(p); q[6] = None
+    arr = (ctypes.c_int32 * 2)(1, 2)
+    assert lib.hmar_attn_bwd_noalloc(*q, arr, 2, 1, 1, 64, 0.0, None) == 1
+
+
 COUNT_SCHEDULES = [(2, 6, 12, 20), (1, 3, 3, 7), (5,), (130, 70, 300), (1, 2, 6, 12, 20, 30, 56, 90, 156, 240)]
 
 
