@@ -8,7 +8,7 @@ resident in HBM before the timed region.  Prints ONE JSON line.
   value      useful TFLOP/s, fwd+bwd: (4 + 10) * D * A * B * H flops per step, A = number of
              unmasked (query, key) pairs per head; element-exact, independent of tile sizes
   roofline   the kernel with the largest share of the step, against the roof that bounds it
-  cpu_baseline  the fp64 oracle timed on the host cores on a sample of heads of the same shape
+  cpu_baseline  the fp64 oracle timed on the host cores on the same workload (every head once)
 """
 from __future__ import annotations
 
@@ -30,16 +30,20 @@ METRIC = "useful TFLOP/s fwd+bwd (680 tok, H=24, D=64) and % of bf16 MFMA peak"
 
 
 def kernel_models(n_heads: int, L: int, D: int, A: int):
-    """Algorithmic bytes and useful flops of one launch of each kernel (inputs read once,
-    outputs written once; re-reads served by cache are not counted)."""
+    """Algorithmic bytes and flops of one launch of each kernel (inputs read once, outputs
+    written once; re-reads served by cache are not counted).
+    `flops` are the contractions the kernel EXECUTES over the unmasked pairs; `useful_flops`
+    what the method needs of them: the backward's scores and dP are formed by both of its
+    kernels but count once (with the dQ kernel, which runs first), so the dK/dV kernel
+    executes four contractions of which two are useful: 2 + 5 useful per pair and D in all."""
     row = D * 2                                  # one bf16 row
     rows = n_heads * L
     pair_flops = 2 * D * A * n_heads             # one contraction over all unmasked pairs
     return {
-        "hmar_fwd_kernel": {"bytes": rows * (4 * row + 4), "flops": 2 * pair_flops},
-        "hmar_dkdv_kernel": {"bytes": rows * (6 * row + 8), "flops": 4 * pair_flops},
+        "hmar_fwd_kernel": {"bytes": rows * (4 * row + 4), "flops": 2 * pair_flops, "useful_flops": 2 * pair_flops},
+        "hmar_dkdv_kernel": {"bytes": rows * (6 * row + 8), "flops": 4 * pair_flops, "useful_flops": 2 * pair_flops},
         # dQ also reads O and LSE and writes the two per-row statistics of the backward
-        "hmar_dq_kernel": {"bytes": rows * (6 * row + 12), "flops": 3 * pair_flops},
+        "hmar_dq_kernel": {"bytes": rows * (6 * row + 12), "flops": 3 * pair_flops, "useful_flops": 3 * pair_flops},
     }
 
 
@@ -60,9 +64,11 @@ def read_traffic(kernel: str):
     return None
 
 
-def cpu_baseline(w, A: int, budget_s: float = 15.0):
-    """Time the oracle (as it stands) on a bounded sample of heads of the same workload."""
-    import numpy as np
+def cpu_baseline(w, A: int, budget_s: float = 30.0, chunk: int = 16):
+    """Time the oracle (as it stands) on the host cores: the WHOLE workload, every head once, in
+    chunks of heads so that the fp64 tensors stay small.  Should the budget run out first, the
+    heads done so far are the sample and the line says so."""
+    import torch
     import synth_inputs as si
     from oracle import hmar_attn_oracle as orc
     try:
@@ -70,42 +76,46 @@ def cpu_baseline(w, A: int, budget_s: float = 15.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    heads = 8
-    Q, K, V, dO = (si.to_f64(t) for t in si.make_inputs(w, heads=heads))
+    Q, K, V, dO = si.make_inputs(w)
+    n_heads = w.B * w.H
+    flat = [t.reshape(1, n_heads, w.L, w.D) for t in (Q, K, V, dO)]
 
-    def run():
-        orc.attn_fwd(Q, K, V, w.sides)
-        orc.attn_bwd(Q, K, V, dO, w.sides)
+    def run(h0, h1):
+        q, k, v, g = (si.to_f64(t[:, h0:h1]) for t in flat)
+        orc.attn_fwd(q, k, v, w.sides)
+        orc.attn_bwd(q, k, v, g, w.sides)
 
-    run()                                         # warm-up (BLAS threads, page faults)
-    t0 = time.perf_counter()
-    run()
-    once = time.perf_counter() - t0
-    reps = max(1, min(200, int(budget_s / max(once, 1e-3))))
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        run()
-    dt = (time.perf_counter() - t0) / reps
-    flops = 14 * w.D * A * heads
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{heads} of {w.B * w.H} heads of {w.name} (fp64 dense masked fwd+bwd), "
-                      f"{reps} repetitions, {dt:.3f} s each",
-            "seconds_per_head": dt / heads}
+    run(0, min(chunk, n_heads))                   # warm-up (BLAS threads, page faults), untimed
+    done, spent = 0, 0.0
+    while done < n_heads and spent < budget_s:
+        h1 = min(done + chunk, n_heads)
+        t0 = time.perf_counter()
+        run(done, h1)
+        spent += time.perf_counter() - t0
+        done = h1
+    flops = 14 * w.D * A * done
+    whole = "the whole workload" if done == n_heads else f"the first {done} heads (time budget {budget_s:.0f} s)"
+    return {"value": flops / spent / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{whole}: {done} of {n_heads} heads of {w.name}, fp64 dense masked fwd+bwd, once, "
+                      f"{chunk} heads per call, {spent:.2f} s (input widening to fp64 included)",
+            "seconds": spent, "seconds_per_head": spent / done}
 
 
-def other_workloads(hm, si, torch, dev, reps: int = 20):
+def other_workloads(hm, si, torch, dev, reps: int = 24):
     """Context figures for the other shapes and entry points (GPU time from HIP events on the
-    launch stream, eager launches, one buffer set): not the headline, not part of `value`."""
-    def gpu_ms(fn):
-        for _ in range(3):
-            fn()
+    launch stream, eager launches): not the headline, not part of `value`.  Each shape rotates
+    through enough buffer sets that a launch never finds its operands in the 256 MB last-level
+    cache from the launch before (working sets: 180 MB to 670 MB per set)."""
+    def gpu_ms(fn, n=reps):
+        for i in range(3):
+            fn(i)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(reps):
-            fn()
+        for i in range(n):
+            fn(i)
         e1.record()
         e1.synchronize()
-        return e0.elapsed_time(e1) / reps
+        return e0.elapsed_time(e1) / n
 
     res = {}
     g = torch.Generator(device=dev)
@@ -117,12 +127,23 @@ def other_workloads(hm, si, torch, dev, reps: int = 20):
     for name, mask in (("256px_b16_h16", 0), ("256px_b32_h30", 0), ("512px_b8_h24", 0), ("256px_b32_h24", 1)):
         w = si.WORKLOADS[name]
         shape = (w.B, w.H, w.L, w.D)
-        q, k, v, do = rnd(shape), rnd(shape), rnd(shape), rnd(shape)
-        O, LSE = hm.hmar_attn_fwd_masked(q, k, v, w.sides, mask)
-        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        one_set = 8 * w.B * w.H * w.L * w.D * 2
+        n_sets = max(2, min(4, -(-600_000_000 // one_set)))
+        sets = []
+        for _ in range(n_sets):
+            q, k, v, do = rnd(shape), rnd(shape), rnd(shape), rnd(shape)
+            O, LSE = hm.hmar_attn_fwd_masked(q, k, v, w.sides, mask)
+            sets.append((q, k, v, do, O, LSE, torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)))
         ws = torch.empty(hm.hmar_attn_bwd_workspace_bytes(w.sides, w.B, w.H, w.D), dtype=torch.uint8, device=dev)
-        f_ms = gpu_ms(lambda: hm.hmar_attn_fwd_masked(q, k, v, w.sides, mask, 0.0, O, LSE))
-        b_ms = gpu_ms(lambda: hm.hmar_attn_bwd_masked(q, k, v, O, do, LSE, w.sides, mask, 0.0, dq, dk, dv, ws))
+
+        def f(i):
+            q, k, v, do, O, LSE, dq, dk, dv = sets[i % n_sets]
+            hm.hmar_attn_fwd_masked(q, k, v, w.sides, mask, 0.0, O, LSE)
+
+        def b(i):
+            q, k, v, do, O, LSE, dq, dk, dv = sets[i % n_sets]
+            hm.hmar_attn_bwd_masked(q, k, v, O, do, LSE, w.sides, mask, 0.0, dq, dk, dv, ws)
+        f_ms, b_ms = gpu_ms(f), gpu_ms(b)
         n = [s * s for s in w.sides]
         if mask == 0:
             A = sum(n[i] * (n[i] + (n[i - 1] if i else 0)) for i in range(len(n)))
@@ -131,31 +152,43 @@ def other_workloads(hm, si, torch, dev, reps: int = 20):
         flops = 2 * w.D * A * w.B * w.H
         res[name + ("_block_causal" if mask else "")] = {
             "fwd_ms": f_ms, "bwd_ms": b_ms, "fwd_tflops": 2 * flops / f_ms / 1e9, "bwd_tflops": 5 * flops / b_ms / 1e9,
-            "fwd_bwd_tflops": 7 * flops / (f_ms + b_ms) / 1e9}
-        del q, k, v, do, O, LSE, dq, dk, dv, ws
+            "fwd_bwd_tflops": 7 * flops / (f_ms + b_ms) / 1e9, "buffer_sets": n_sets}
+        del sets, ws
     # KV-cache-free inference: the 10 steps of the 256px schedule, B = 64, H = 24, forward only
+    # (706 MB per sweep, two buffer sets): all ten steps in ONE call, and one call per step
     w = si.WORKLOADS["256px_b32_h24"]
     B, H, D = 64, 24, 64
     n = [s * s for s in w.sides]
-    steps = []
-    for i, n_cur in enumerate(n):
-        n_prev = n[i - 1] if i else 0
-        q = rnd((B, H, n_cur, D))
-        k, v = rnd((B, H, n_prev + n_cur, D)), rnd((B, H, n_prev + n_cur, D))
-        O = torch.empty_like(q)
-        LSE = torch.empty((B, H, n_cur), dtype=torch.float32, device=dev)
-        steps.append((q, k, v, n_prev, O, LSE))
+    n_prevs = [n[i - 1] if i else 0 for i in range(len(n))]
+    sweeps = []
+    for _ in range(2):
+        qs = [rnd((B, H, c, D)) for c in n]
+        ks = [rnd((B, H, p + c, D)) for p, c in zip(n_prevs, n)]
+        vs = [rnd((B, H, p + c, D)) for p, c in zip(n_prevs, n)]
+        os_ = [torch.empty_like(q) for q in qs]
+        ls = [torch.empty((B, H, c), dtype=torch.float32, device=dev) for c in n]
+        sweeps.append((qs, ks, vs, os_, ls))
 
-    def sweep():
-        for (q, k, v, n_prev, O, LSE) in steps:
-            hm.hmar_attn_step_fwd(q, k, v, n_prev, 0.0, O, LSE)
-    ms = gpu_ms(sweep)
-    pairs = sum(n[i] * (n[i] + (n[i - 1] if i else 0)) for i in range(len(n)))
+    def batched(i):
+        qs, ks, vs, os_, ls = sweeps[i % 2]
+        hm.hmar_attn_steps_fwd(qs, ks, vs, n_prevs, 0.0, os_, ls)
+
+    def one_by_one(i):
+        qs, ks, vs, os_, ls = sweeps[i % 2]
+        for j in range(len(n)):
+            hm.hmar_attn_step_fwd(qs[j], ks[j], vs[j], n_prevs[j], 0.0, os_[j], ls[j])
+
+    def last_only(i):
+        qs, ks, vs, os_, ls = sweeps[i % 2]
+        hm.hmar_attn_step_fwd(qs[-1], ks[-1], vs[-1], n_prevs[-1], 0.0, os_[-1], ls[-1])
+    ms, ms_single, last = gpu_ms(batched), gpu_ms(one_by_one), gpu_ms(last_only)
+    pairs = sum(n[i] * (n[i] + n_prevs[i]) for i in range(len(n)))
     flops = 4 * D * pairs * B * H
-    nbytes = B * H * sum((2 * n[i] + 2 * (n[i] + (n[i - 1] if i else 0))) * D * 2 + 4 * n[i] for i in range(len(n)))
-    last = gpu_ms(lambda: hm.hmar_attn_step_fwd(*steps[-1][:4], 0.0, steps[-1][4], steps[-1][5]))
+    nbytes = B * H * sum((2 * n[i] + 2 * (n[i] + n_prevs[i])) * D * 2 + 4 * n[i] for i in range(len(n)))
     res["inference_steps_256px_b64_h24"] = {
-        "all_10_steps_ms": ms, "tflops": flops / ms / 1e9, "hbm_gbs": nbytes / ms / 1e6,
+        "all_10_steps_ms": ms, "launch": "one hmar_attn_steps_fwd call (one kernel launch)",
+        "tflops": flops / ms / 1e9, "hbm_gbs": nbytes / ms / 1e6,
+        "ten_single_step_calls_ms": ms_single,
         "last_step_ms": last, "last_step_tflops": 4 * D * n[-1] * (n[-1] + n[-2]) * B * H / last / 1e9}
     return res
 
@@ -314,8 +347,10 @@ def main() -> int:
     roof["kernel"] = dominant
     roof["kernel_ms"] = kern_ms[dominant]
     roof["algorithmic_bytes"] = m["bytes"]
-    roof["useful_flops"] = m["flops"]
-    roof["mfma_frac"] = m["flops"] / t_dom / 1e12 / MFMA_PEAK_TFLOPS
+    roof["executed_flops"] = m["flops"]
+    roof["useful_flops"] = m["useful_flops"]
+    roof["mfma_frac_executed"] = m["flops"] / t_dom / 1e12 / MFMA_PEAK_TFLOPS
+    roof["mfma_frac_useful"] = m["useful_flops"] / t_dom / 1e12 / MFMA_PEAK_TFLOPS
     roof["hbm_frac"] = m["bytes"] / t_dom / 1e9 / HBM_PEAK_GBS
 
     flops_fwd = 4 * w.D * A * n_heads

@@ -37,6 +37,10 @@ def test_kernel_byte_and_flop_models_match_the_schedule_arithmetic():
     assert m["hmar_fwd_kernel"]["flops"] == 2 * unit
     assert m["hmar_dkdv_kernel"]["flops"] == 4 * unit
     assert m["hmar_dq_kernel"]["flops"] == 3 * unit
+    # useful flops: the recomputed S and dP count once, so the per-kernel figures add up to the
+    # 2 + 5 contractions of the headline metric
+    assert sum(k["useful_flops"] for k in m.values()) == (2 + 5) * unit
+    assert m["hmar_dkdv_kernel"]["useful_flops"] == 2 * unit
     assert abs((2 + 5) * unit / 1e9 - 124.43) < 0.01              # the headline figure per step
     assert bench.METRIC.startswith("useful TFLOP/s fwd+bwd (680 tok, H=24, D=64)")
 
