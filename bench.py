@@ -47,10 +47,10 @@ def kernel_models(n_heads: int, L: int, D: int, A: int):
     }
 
 
-def read_traffic(kernel: str):
+def read_traffic(kernel: str, workload: str = WORKLOAD):
     """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
     kept as `kernel = bytes` lines in profiles/hbm_traffic_<workload>.txt; None if absent."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{WORKLOAD}.txt")
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
     try:
         with open(path) as f:
             for line in f:
@@ -203,6 +203,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary workloads (context only)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays")
+    ap.add_argument("--workload", default=WORKLOAD,
+                    help="time another training shape of synth_inputs.WORKLOADS instead (for profiling it; the "
+                         "headline line is the default workload's)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch the plain copy kernel (for rocprofv3 --pmc traffic calibration)")
     args = ap.parse_args()
@@ -218,7 +221,7 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("no GPU visible: this benchmark has no CPU path", file=sys.stderr)
         return 3
-    w = si.WORKLOADS[WORKLOAD]
+    w = si.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     offs, A = hm.hmar_schedule_describe(w.sides)
@@ -343,7 +346,7 @@ def main() -> int:
         achieved = m["flops"] / t_dom / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MFMA_PEAK_TFLOPS}
-    roof["traffic"] = read_traffic(dominant)
+    roof["traffic"] = read_traffic(dominant, w.name)
     roof["kernel"] = dominant
     roof["kernel_ms"] = kern_ms[dominant]
     roof["algorithmic_bytes"] = m["bytes"]

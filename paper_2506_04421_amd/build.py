@@ -24,20 +24,35 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every source and link the shared library.  Always recompiles."""
+def variant_path(name: str) -> str:
+    """Where a measurement variant of the library is written (never the library the package loads)."""
+    return os.path.join(HERE, f"libhmar_attn_{name}.so")
+
+
+def build_library(verbose: bool = False, variant: str = "", defines=()) -> str:
+    """Compile every source and link the shared library.  Always recompiles.
+    With `variant`, builds libhmar_attn_<variant>.so with the given -D knobs (see the list at the
+    top of csrc/device_common.h) next to the library instead: for measurements only."""
+    out = variant_path(variant) if variant else LIB_PATH
     cmd = [hipcc_path(), "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip", *DEVICE_FLAGS,
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH + ".tmp"]
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, *[f"-D{d}" for d in defines],
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", out + ".tmp"]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("hipcc failed building libhmar_attn.so")
-    os.replace(LIB_PATH + ".tmp", LIB_PATH)
-    return LIB_PATH
+        raise RuntimeError(f"hipcc failed building {os.path.basename(out)}")
+    os.replace(out + ".tmp", out)
+    return out
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--variant", default="", help="build libhmar_attn_<variant>.so for measurements")
+    ap.add_argument("-D", dest="defines", action="append", default=[], help="macro for the variant, e.g. -DHMAR_TUNE_LDS_PAD_FWD=32768")
+    a = ap.parse_args()
+    if a.defines and not a.variant:
+        ap.error("-D knobs need --variant: the library the package loads is always built without them")
+    print(build_library(verbose=True, variant=a.variant, defines=a.defines))

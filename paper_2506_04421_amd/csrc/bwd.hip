@@ -42,6 +42,9 @@ struct BwdParams {
 __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(BwdParams p) {
     // ring of 2 stages, each a K tile followed by a V tile
     __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+#ifdef HMAR_TUNE_LDS_PAD_DQ
+    HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_DQ)
+#endif
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id, true)) return;
@@ -49,8 +52,9 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
-    const __bf16* Kh = p.K + head_off;
-    const __bf16* Vh = p.V + head_off;
+    const size_t head_in = (size_t)HMAR_INPUT_HEAD(head) * p.L * kD;     // == head_off outside measurements
+    const __bf16* Kh = p.K + head_in;
+    const __bf16* Vh = p.V + head_in;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
     const uint32_t smem_base = lds_address(smem);
 
@@ -76,17 +80,17 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
     bf16x8 q[4], dob[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        q[t] = *reinterpret_cast<const bf16x8*>(p.Q + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
-        dob[t] = *reinterpret_cast<const bf16x8*>(p.dO + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
+        q[t] = *reinterpret_cast<const bf16x8*>(p.Q + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
+        dob[t] = *reinterpret_cast<const bf16x8*>(p.dO + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
     }
     // -Delta of this lane's row: each half-wave holds 32 of the row's 64 dO values
-    const float nl2 = -p.LSE[(size_t)head * p.L + qrow] * kLog2e;
+    const float nl2 = -p.LSE[(size_t)HMAR_INPUT_HEAD(head) * p.L + qrow] * kLog2e;
     float ndelta;
     {
         float acc = 0.f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const bf16x8 ov = *reinterpret_cast<const bf16x8*>(p.O + head_off + (size_t)qrow * kD + 16 * t + 8 * h);
+            const bf16x8 ov = *reinterpret_cast<const bf16x8*>(p.O + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
             const bf16x8 gv = dob[t];
             // two products per instruction (v_dot2c_f32_bf16), fp32 accumulation
             acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 0, 1), __builtin_shufflevector(gv, gv, 0, 1), acc, false);
@@ -119,7 +123,11 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         constexpr int ST = decltype(stage_c)::value;
         const int kt = k_begin + ti * kTile;
         if (ti + 1 < ntiles) issue(ti + 1, ST ^ 1);
+#ifdef HMAR_TUNE_NO_COMPUTE_DQ
+        if (false) {
+#else
         if (wave_active && kt < whi && kt + kTile > wlo) {
+#endif
             const uint32_t Kt = smem_base + ST * (2 * kTileBytes);
             const uint32_t Vt = Kt + kTileBytes;
             const bool need_lo = kt < full_lo, need_hi = kt + kTile > full_hi;
@@ -178,6 +186,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
     __shared__ __attribute__((aligned(256))) float nl2_s[2][kTile];
     __shared__ __attribute__((aligned(256))) float delta_s[2][kTile];
+#ifdef HMAR_TUNE_LDS_PAD_DKDV
+    HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_DKDV)
+#endif
 
     int head, item_id;
     if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id)) return;
@@ -185,8 +196,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
-    const __bf16* Qh = p.Q + head_off;
-    const __bf16* Gh = p.dO + head_off;
+    const size_t head_in = (size_t)HMAR_INPUT_HEAD(head) * p.L * kD;     // == head_off outside measurements
+    const __bf16* Qh = p.Q + head_in;
+    const __bf16* Gh = p.dO + head_in;
     const float* NLh = p.neg_lse2 + (size_t)head * p.L;
     const float* Dh = p.neg_delta + (size_t)head * p.L;
     const LaneOffsets lo_ = make_lane_offsets(lane, wave);
@@ -219,8 +231,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     bf16x8 kreg[4], vreg[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        kreg[t] = *reinterpret_cast<const bf16x8*>(p.K + head_off + (size_t)krow * kD + 16 * t + 8 * h);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(p.V + head_off + (size_t)krow * kD + 16 * t + 8 * h);
+        kreg[t] = *reinterpret_cast<const bf16x8*>(p.K + head_in + (size_t)krow * kD + 16 * t + 8 * h);
+        vreg[t] = *reinterpret_cast<const bf16x8*>(p.V + head_in + (size_t)krow * kD + 16 * t + 8 * h);
     }
 
     f32x16 dk[2], dv[2];
@@ -237,7 +249,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
         constexpr int ST = decltype(stage_c)::value;
         const int qt = q_begin + ti * kTile;
         if (ti + 1 < ntiles) issue(ti + 1, ST ^ 1);
+#ifdef HMAR_TUNE_NO_COMPUTE_DKDV
+        if (false) {
+#else
         if (wave_active && qt < whi && qt + kTile > wlo) {
+#endif
             const uint32_t Qt = smem_base + ST * (2 * kTileBytes);
             const uint32_t Gt = Qt + kTileBytes;
             const uint32_t nl2_t = nl2_base + ST * (kTile * 4) + 16 * h;

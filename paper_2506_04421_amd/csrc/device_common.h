@@ -55,6 +55,27 @@ constexpr float kNegBig = -1.0e30f;
 
 struct alignas(16) Item { int32_t own_begin, own_end, other_begin, other_end; };
 
+// ---- build-time knobs for measurements (never set in the library the tests and the benchmark
+// load; `python -m paper_2506_04421_amd.build --variant NAME -D...` builds a separate library):
+//   HMAR_TUNE_LDS_PAD_FWD / _DQ / _DKDV = bytes   extra LDS per workgroup: caps the workgroups a CU
+//                                                 holds, i.e. the wavefronts per SIMD of that kernel
+//   HMAR_TUNE_NO_COMPUTE_FWD / _DQ / _DKDV        skip the tile arithmetic: what remains is the
+//                                                 kernel's memory skeleton (loads, barriers, stores)
+//   HMAR_TUNE_ALIAS_HEADS                         every head reads the inputs of head (head % 8): the
+//                                                 loads then hit in L2 and no HBM read remains
+//   HMAR_TUNE_FWD_STUDY (+ HMAR_STUDY_*)          the forward of tuning/fwd_tile_study.inc instead: rows
+//                                                 per wavefront, key tile, software pipelining
+#if defined(HMAR_TUNE_ALIAS_HEADS)
+#define HMAR_INPUT_HEAD(h) ((h) & 7)
+#else
+#define HMAR_INPUT_HEAD(h) (h)
+#endif
+// extra LDS, kept allocated by an address use the compiler cannot remove
+#define HMAR_TUNE_LDS_PAD(BYTES)                                                \
+    __shared__ char hmar_tune_pad[(BYTES) > 0 ? (BYTES) : 1];                   \
+    if ((BYTES) > 0) asm volatile("" :: "v"(lds_address(hmar_tune_pad)));
+
+
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 

@@ -10,6 +10,7 @@
 // second contraction O^T += V^T P^T, whose A operand comes from the row-major V tile
 // through the LDS transpose load.
 #include <type_traits>
+#include <utility>
 
 #include "device_common.h"
 #include "kernels.h"
@@ -75,17 +76,17 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
         it.own_end = min(sd.n_q, it.own_begin + 128);
         it.other_begin = 0;
         it.other_end = sd.Lk;
-        const size_t q_off = (size_t)head * sd.q_stride;
-        Qh = sd.Q + q_off * kD; Oh = sd.O + q_off * kD; LSEh = sd.LSE + q_off;
-        Kh = sd.K + (size_t)head * sd.Lk * kD;
-        Vh = sd.V + (size_t)head * sd.Lk * kD;
+        const size_t q_off = (size_t)head * sd.q_stride, q_in = (size_t)HMAR_INPUT_HEAD(head) * sd.q_stride;
+        Qh = sd.Q + q_in * kD; Oh = sd.O + q_off * kD; LSEh = sd.LSE + q_off;
+        Kh = sd.K + (size_t)HMAR_INPUT_HEAD(head) * sd.Lk * kD;
+        Vh = sd.V + (size_t)HMAR_INPUT_HEAD(head) * sd.Lk * kD;
         rows = sd.rows;
     } else {
         it = p.items[item_id];
-        const size_t q_off = (size_t)head * p.L;
-        Qh = p.Q + q_off * kD; Oh = p.O + q_off * kD; LSEh = p.LSE + q_off;
-        Kh = p.K + (size_t)head * p.Lk * kD;
-        Vh = p.V + (size_t)head * p.Lk * kD;
+        const size_t q_off = (size_t)head * p.L, q_in = (size_t)HMAR_INPUT_HEAD(head) * p.L;
+        Qh = p.Q + q_in * kD; Oh = p.O + q_off * kD; LSEh = p.LSE + q_off;
+        Kh = p.K + (size_t)HMAR_INPUT_HEAD(head) * p.Lk * kD;
+        Vh = p.V + (size_t)HMAR_INPUT_HEAD(head) * p.Lk * kD;
         row_lo = p.row_lo; row_hi = p.row_hi;
     }
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -149,7 +150,11 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
         const int kt = k_begin + ti * kTile;
         // the next tile goes into the other stage, which every wavefront left at the last barrier
         if (ti + 1 < ntiles) issue(ti + 1, ST ^ 1);
+#ifdef HMAR_TUNE_NO_COMPUTE_FWD
+        if (false) {
+#else
         if (wave_active && kt < whi && kt + kTile > wlo) {
+#endif
             const uint32_t Kt = smem_base + ST * (2 * kTileBytes);
             const uint32_t Vt = Kt + kTileBytes;
             f32x16 s[2];
@@ -223,6 +228,9 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
 __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(FwdParams p) {
     // ring of 2 stages, each a K tile followed by a V tile
     __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+#ifdef HMAR_TUNE_LDS_PAD_FWD
+    HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_FWD)
+#endif
     fwd_body<false>(p, smem);
 }
 
@@ -230,6 +238,23 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_steps_k
     __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
     fwd_body<true>(p, smem);
 }
+
+#ifdef HMAR_TUNE_FWD_STUDY
+#include "../tuning/fwd_tile_study.inc"
+#ifndef HMAR_STUDY_RB
+#define HMAR_STUDY_RB 1
+#endif
+#ifndef HMAR_STUDY_NW
+#define HMAR_STUDY_NW 4
+#endif
+#ifndef HMAR_STUDY_PIPE
+#define HMAR_STUDY_PIPE 0
+#endif
+#ifndef HMAR_STUDY_MINW
+#define HMAR_STUDY_MINW 4
+#endif
+static_assert(HMAR_STUDY_RB * HMAR_STUDY_NW == 4, "items of the forward list own up to 128 rows");
+#endif
 
 hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
                       const DeviceSchedule& s, int n_heads, float sm_scale, hipStream_t stream) {
@@ -251,7 +276,12 @@ hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, floa
     const long long groups = 8LL * ((n_heads + 7) / 8) * s.n_items[0];
     if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
     profile_before(kKernelFwd, stream);
+#ifdef HMAR_TUNE_FWD_STUDY
+    hipLaunchKernelGGL((hmar_fwd_study_kernel<HMAR_STUDY_RB, HMAR_STUDY_NW, HMAR_STUDY_MINW, HMAR_STUDY_PIPE != 0>),
+                       dim3((unsigned)groups), dim3(64 * HMAR_STUDY_NW), 0, stream, p);
+#else
     hipLaunchKernelGGL(hmar_fwd_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+#endif
     const hipError_t e = hipGetLastError();
     profile_after(kKernelFwd, stream);
     return e;
