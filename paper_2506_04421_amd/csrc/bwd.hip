@@ -345,6 +345,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     }
 }
 
+#if defined(HMAR_DKDV_PIPE) || (defined(HMAR_DKDV_KEYS_PER_WAVE) && HMAR_DKDV_KEYS_PER_WAVE == 16)
+#include "../tuning/dkdv_variants.inc"
+#endif
+
 // Plain copy, 16 bytes per lane, grid-stride: calibration of the HBM traffic counters.
 __global__ __launch_bounds__(256) void hmar_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src,
                                                         size_t n16) {
@@ -361,6 +365,10 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t str
                        static_cast<const u32x4*>(src), n16);
     return hipGetLastError();
 }
+
+#ifndef HMAR_DKDV_KEYS_PER_WAVE
+#define HMAR_DKDV_KEYS_PER_WAVE 32
+#endif
 
 hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                       const float* LSE, void* dQ, void* dK, void* dV, float* workspace,
@@ -394,7 +402,13 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
         if (groups <= 0 || groups > 0x7fffffffLL) return hipErrorInvalidValue;
         const int kid = dir == 1 ? kKernelDkDv : kKernelDq;
         profile_before(kid, stream);
+#if HMAR_DKDV_KEYS_PER_WAVE == 16
+        if (dir == 1) hipLaunchKernelGGL(hmar_dkdv16_kernel, dim3((unsigned)groups), dim3(kThreads16), 0, stream, p);
+#elif defined(HMAR_DKDV_PIPE)
+        if (dir == 1) hipLaunchKernelGGL(hmar_dkdv_pipe_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+#else
         if (dir == 1) hipLaunchKernelGGL(hmar_dkdv_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+#endif
         else          hipLaunchKernelGGL(hmar_dq_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
         const hipError_t e = hipGetLastError();
         profile_after(kid, stream);

@@ -65,6 +65,9 @@ struct alignas(16) Item { int32_t own_begin, own_end, other_begin, other_end; };
 //                                                 loads then hit in L2 and no HBM read remains
 //   HMAR_TUNE_FWD_STUDY (+ HMAR_STUDY_*)          the forward of tuning/fwd_tile_study.inc instead: rows
 //                                                 per wavefront, key tile, software pipelining
+//   HMAR_DKDV_PIPE / HMAR_DKDV_KEYS_PER_WAVE=16   a dK/dV kernel of tuning/dkdv_variants.inc instead: scores
+//                                                 formed one block ahead / 16 keys per wavefront on
+//                                                 16x16x32 MFMAs at four wavefronts per SIMD
 #if defined(HMAR_TUNE_ALIAS_HEADS)
 #define HMAR_INPUT_HEAD(h) ((h) & 7)
 #else
