@@ -39,16 +39,28 @@ struct BwdParams {
 #ifndef HMAR_DQ_MIN_WAVES
 #define HMAR_DQ_MIN_WAVES 4
 #endif
-__global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(BwdParams p) {
-    // ring of 2 stages, each a K tile followed by a V tile
-    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
-#ifdef HMAR_TUNE_LDS_PAD_DQ
-    HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_DQ)
-#endif
+// -Delta of a row from the lane's half of it: each half-wave holds 32 of the row's 64 dO values
+__device__ __forceinline__ float neg_delta_of_row(const __bf16* o_row, const bf16x8 (&dob)[4], int h) {
+    float acc = 0.f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const bf16x8 ov = *reinterpret_cast<const bf16x8*>(o_row + 16 * t + 8 * h);
+        const bf16x8 gv = dob[t];
+        // two products per instruction (v_dot2c_f32_bf16), fp32 accumulation
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 0, 1), __builtin_shufflevector(gv, gv, 0, 1), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 2, 3), __builtin_shufflevector(gv, gv, 2, 3), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 4, 5), __builtin_shufflevector(gv, gv, 4, 5), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 6, 7), __builtin_shufflevector(gv, gv, 6, 7), acc, false);
+    }
+    return -half_sum(acc);
+}
 
-    int head, item_id;
-    if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id, true)) return;
-    const Item it = p.items[item_id];
+// The work of one dQ item.  smem: ring of 2 stages, each a K tile followed by a V tile.
+// OWN_STATS: form the row statistics here and leave them in the workspace (the shipped kernel);
+// otherwise they are read from the workspace.
+template <bool OWN_STATS>
+__device__ __forceinline__ void dq_body(const BwdParams& p, const Item it, const int32_t* row_lo, const int32_t* row_hi,
+                                        int head, int item_id, char* smem) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
@@ -71,11 +83,11 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;
     const int qrow = min(wq0 + lr, it.own_end - 1);
-    const int lo = p.row_lo[qrow], hi = p.row_hi[qrow];
+    const int lo = row_lo[qrow], hi = row_hi[qrow];
     // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
     const int rfirst = min(wq0, it.own_end - 1), rlast = min(wq0 + kRowsPerWave - 1, it.own_end - 1);
-    const int wlo = p.row_lo[rfirst], whi = p.row_hi[rlast];        // union of the wavefront's ranges
-    const int full_lo = p.row_lo[rlast], full_hi = p.row_hi[rfirst];  // what every one of its rows pairs with
+    const int wlo = row_lo[rfirst], whi = row_hi[rlast];        // union of the wavefront's ranges
+    const int full_lo = row_lo[rlast], full_hi = row_hi[rfirst];  // what every one of its rows pairs with
 
     bf16x8 q[4], dob[4];
 #pragma unroll
@@ -83,26 +95,17 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         q[t] = *reinterpret_cast<const bf16x8*>(p.Q + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
         dob[t] = *reinterpret_cast<const bf16x8*>(p.dO + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
     }
-    // -Delta of this lane's row: each half-wave holds 32 of the row's 64 dO values
-    const float nl2 = -p.LSE[(size_t)HMAR_INPUT_HEAD(head) * p.L + qrow] * kLog2e;
-    float ndelta;
-    {
-        float acc = 0.f;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const bf16x8 ov = *reinterpret_cast<const bf16x8*>(p.O + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
-            const bf16x8 gv = dob[t];
-            // two products per instruction (v_dot2c_f32_bf16), fp32 accumulation
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 0, 1), __builtin_shufflevector(gv, gv, 0, 1), acc, false);
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 2, 3), __builtin_shufflevector(gv, gv, 2, 3), acc, false);
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 4, 5), __builtin_shufflevector(gv, gv, 4, 5), acc, false);
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 6, 7), __builtin_shufflevector(gv, gv, 6, 7), acc, false);
+    float nl2, ndelta;
+    if constexpr (OWN_STATS) {
+        nl2 = -p.LSE[(size_t)HMAR_INPUT_HEAD(head) * p.L + qrow] * kLog2e;
+        ndelta = neg_delta_of_row(p.O + head_in + (size_t)qrow * kD, dob, h);
+        if (wq0 + lr < it.own_end && h == 0) {
+            p.neg_lse2[(size_t)head * p.L + qrow] = nl2;
+            p.neg_delta[(size_t)head * p.L + qrow] = ndelta;
         }
-        ndelta = -half_sum(acc);
-    }
-    if (wq0 + lr < it.own_end && h == 0) {
-        p.neg_lse2[(size_t)head * p.L + qrow] = nl2;
-        p.neg_delta[(size_t)head * p.L + qrow] = ndelta;
+    } else {
+        nl2 = p.neg_lse2[(size_t)head * p.L + qrow];
+        ndelta = p.neg_delta[(size_t)head * p.L + qrow];
     }
 
     f32x16 dq[2];
@@ -173,6 +176,16 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
         store_block_rows(smem_base + wave * kPatchBytes, dq, p.sm_scale, p.dQ + head_off, wq0, it.own_end - wq0, lane);
 }
 
+__global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(BwdParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+#ifdef HMAR_TUNE_LDS_PAD_DQ
+    HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_DQ)
+#endif
+    int head, item_id;
+    if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id, true)) return;
+    dq_body<true>(p, p.items[item_id], p.row_lo, p.row_hi, head, item_id, smem);
+}
+
 // ---------------------------------------------------------------------------------- dK, dV
 // Register budget: the two result accumulators, the own K and V rows, both blocks' scores and
 // the batched LDS operands need about 250 VGPRs, which means two wavefronts per SIMD (two
@@ -181,18 +194,10 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 #ifndef HMAR_DKDV_MIN_WAVES
 #define HMAR_DKDV_MIN_WAVES 2
 #endif
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_DKDV_MIN_WAVES, HMAR_DKDV_MIN_WAVES))) void hmar_dkdv_kernel(BwdParams p) {
-    // ring of 2 stages, each a Q tile followed by a dO tile; then the per-row statistics
-    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
-    __shared__ __attribute__((aligned(256))) float nl2_s[2][kTile];
-    __shared__ __attribute__((aligned(256))) float delta_s[2][kTile];
-#ifdef HMAR_TUNE_LDS_PAD_DKDV
-    HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_DKDV)
-#endif
-
-    int head, item_id;
-    if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id)) return;
-    const Item it = p.items[item_id];
+// The work of one dK/dV item.  smem: ring of 2 stages, each a Q tile followed by a dO tile;
+// nl2_s, delta_s: the per-row statistics of the two stages.
+__device__ __forceinline__ void dkdv_body(const BwdParams& p, const Item it, const int32_t* row_lo, const int32_t* row_hi,
+                                          int head, int item_id, char* smem, float (*nl2_s)[kTile], float (*delta_s)[kTile]) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 31, h = lane >> 5;
     const size_t head_off = (size_t)head * p.L * kD;
@@ -222,11 +227,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     const int wk0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wk0 < it.own_end;
     const int krow = min(wk0 + lr, it.own_end - 1);
-    const int lo = p.row_lo[krow], hi = p.row_hi[krow];       // queries that see this key
+    const int lo = row_lo[krow], hi = row_hi[krow];       // queries that see this key
     // pair ranges never decrease along the rows: the wavefront's extremes are at its first and last row
     const int rfirst = min(wk0, it.own_end - 1), rlast = min(wk0 + kRowsPerWave - 1, it.own_end - 1);
-    const int wlo = p.row_lo[rfirst], whi = p.row_hi[rlast];        // union of the wavefront's ranges
-    const int full_lo = p.row_lo[rlast], full_hi = p.row_hi[rfirst];  // what every one of its rows pairs with
+    const int wlo = row_lo[rfirst], whi = row_hi[rlast];        // union of the wavefront's ranges
+    const int full_lo = row_lo[rlast], full_hi = row_hi[rfirst];  // what every one of its rows pairs with
 
     bf16x8 kreg[4], vreg[4];
 #pragma unroll
@@ -345,6 +350,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
     }
 }
 
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_DKDV_MIN_WAVES, HMAR_DKDV_MIN_WAVES))) void hmar_dkdv_kernel(BwdParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+    __shared__ __attribute__((aligned(256))) float nl2_s[2][kTile];
+    __shared__ __attribute__((aligned(256))) float delta_s[2][kTile];
+#ifdef HMAR_TUNE_LDS_PAD_DKDV
+    HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_DKDV)
+#endif
+    int head, item_id;
+    if (!map_workgroup(p.n_items, p.n_heads, p.tail_groups, &head, &item_id)) return;
+    dkdv_body(p, p.items[item_id], p.row_lo, p.row_hi, head, item_id, smem, nl2_s, delta_s);
+}
+
+#if defined(HMAR_BWD_MERGED)
+#include "../tuning/bwd_merged.inc"
+#endif
+
 #if defined(HMAR_DKDV_PIPE) || (defined(HMAR_DKDV_KEYS_PER_WAVE) && HMAR_DKDV_KEYS_PER_WAVE == 16)
 #include "../tuning/dkdv_variants.inc"
 #endif
@@ -391,6 +412,9 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
     p.c = sm_scale * kLog2e;
     p.sm_scale = sm_scale;
 
+#if defined(HMAR_BWD_MERGED)
+    return launch_bwd_merged(p, s, n_heads, stream);
+#endif
     // dQ first: it also produces the per-row statistics the dK/dV kernel streams
     for (int dir = 0; dir < 2; ++dir) {
         p.items = static_cast<const Item*>(s.items[dir]);
