@@ -1,6 +1,6 @@
 // Instruction-issue microbenchmark for gfx950: what one SIMD sustains when matrix (MFMA), vector,
 // transcendental and LDS instructions share it.  It fixes the cost model the kernels are judged
-// against ("Machine model"): per-instruction issue times, how much of an MFMA's
+// against: per-instruction issue times, how much of an MFMA's
 // duration vector instructions can use, LDS read bandwidth, and the per-block ceilings of the
 // instruction mixes of the forward, dQ, dK/dV and a hypothetical fused backward.
 //
