@@ -41,9 +41,16 @@ struct StepDesc {
     int Lk;                // key rows
     int first_item;        // index of the step's first item in the launch
 };
+// Steps whose keys fit one tile (Lk <= 64; the first scales of a schedule) are too small to fill a
+// workgroup: they come last in `step` and share ONE item per head, the launch's last, in which
+// every wavefront works on its own: unit u of the pack is the 32-row block pack_unit[u] % 2 of step
+// pack_unit[u] / 2, taken by wavefront u % 4 (see small_steps_pack).
+constexpr int kMaxPackUnits = 2 * kMaxSteps;
 struct StepParams {
-    StepDesc step[kMaxSteps];
-    int n_steps, n_items, n_heads, tail_groups;
+    StepDesc step[kMaxSteps];   // the n_tiled steps that get items of their own, then the packed ones
+    int n_tiled, n_items, n_heads, tail_groups;
+    int n_pack;                 // units of the pack (0: the launch has no pack item)
+    int pack_unit[kMaxPackUnits];
     float c;
 };
 
@@ -56,6 +63,106 @@ constexpr float kRescaleThreshold = 8.0f;
 #ifndef HMAR_FWD_MIN_WAVES
 #define HMAR_FWD_MIN_WAVES 4
 #endif
+
+// The pack item of a steps launch: inference steps with at most 64 keys.  A wavefront takes the
+// units u = wave, wave + 4, ... and computes each alone, without the workgroup: the unit's 32 query
+// rows and the step's key rows go from global memory straight into registers (both are row-wise
+// operands), the value rows go by DMA into the wavefront's own quarter of the ring (8 KB, one
+// tile), from where the transpose load feeds the second contraction; the same quarter then
+// serves as the patch of the result.  One tile holds all keys, so the softmax is the plain
+// one: row maximum, exponentials, row sum.  No barrier: nothing is shared between wavefronts.
+__device__ __forceinline__ void small_steps_pack(const StepParams& p, int head, char* smem) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lr = lane & 31, h = lane >> 5;
+    const LaneOffsets lo_ = make_lane_offsets(lane, 0);
+    const uint32_t Vt = __builtin_amdgcn_readfirstlane(lds_address(smem) + wave * kTileBytes);
+    static_assert(kPatchBytes <= kTileBytes, "the result patch reuses the value tile");
+
+    for (int u = wave; u < p.n_pack; u += 4) {
+        const int unit = p.pack_unit[u];
+        const StepDesc& sd = p.step[unit >> 1];
+        const int n_q = sd.n_q, Lk = sd.Lk;                 // Lk <= 64, no row map
+        const int row0 = 32 * (unit & 1);                   // < n_q
+        const size_t in_head = (size_t)HMAR_INPUT_HEAD(head);
+        const __bf16* Qh = sd.Q + in_head * n_q * kD;
+        const __bf16* Kh = sd.K + in_head * Lk * kD;
+        const __bf16* Vh = sd.V + in_head * Lk * kD;
+        const bool two_blocks = Lk > 32;                    // uniform: keys 32..63 exist
+
+        // value rows: this wavefront moves the whole tile, 8 rows per load, rows clamped to the
+        // last key (every LDS row the contraction reads must hold finite numbers).  The
+        // previous unit's patch reads have been consumed by its stores' operands by now.
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            if (b < 4 || two_blocks) {
+                const int r = 8 * b + (lane >> 3);
+                const uint32_t voff = min(r, Lk - 1) * kRowBytes + (((lane & 7) ^ swz(r)) << 4);
+                dma16(Vh, voff, Vt + b * 1024);
+            }
+        }
+        const int qrow = min(row0 + lr, n_q - 1);
+        bf16x8 q[4], ka[2][4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            q[t] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow * kD + 16 * t + 8 * h);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+                ka[kb][t] = *reinterpret_cast<const bf16x8*>(Kh + (size_t)min(32 * kb + lr, Lk - 1) * kD + 16 * t + 8 * h);
+        }
+        // all twelve loads are in flight before the first one is awaited; loads complete in order,
+        // so the value tile requested before them has landed as well
+        asm volatile("" :: "v"(q[0]), "v"(q[1]), "v"(q[2]), "v"(q[3]), "v"(ka[0][0]), "v"(ka[0][1]), "v"(ka[0][2]),
+                     "v"(ka[0][3]), "v"(ka[1][0]), "v"(ka[1][1]), "v"(ka[1][2]), "v"(ka[1][3]));
+
+        f32x16 s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) s[kb] = mfma32(ka[kb][t], q[t], s[kb]);
+        }
+        // element i of block kb is key 4h + 32kb + 8(i/4) + i%4; keys >= Lk do not exist
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) mask_block(s[kb], 32 * kb, -4 * h, Lk - 4 * h, false, Lk < 64);
+        float mt = s[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mt = fmaxf(mt, s[kb][i]);
+        const float m_ref = half_max(mt) * p.c;            // key 0 exists: finite
+        float lsum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][i], p.c, -m_ref));
+                lsum += pv;
+                s[kb][i] = pv;
+            }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // (already true; the compiler cannot know)
+        f32x16 o[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
+#pragma unroll
+        for (int tp = 0; tp < 4; ++tp) {
+            if (tp < 2 || two_blocks) {
+                const int kb = tp >> 1, e0 = 8 * (tp & 1);
+                const bf16x8 pb = pack8(s[kb][e0 + 0], s[kb][e0 + 1], s[kb][e0 + 2], s[kb][e0 + 3],
+                                        s[kb][e0 + 4], s[kb][e0 + 5], s[kb][e0 + 6], s[kb][e0 + 7]);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) o[mb] = mfma32(lds_a_tr(Vt, lo_, mb, tp), pb, o[mb]);
+            }
+        }
+        const float l = half_sum(lsum);
+        // LDS operations of a wavefront execute in order: the patch writes follow the tile reads
+        store_block_rows(Vt, o, 1.0f / l, sd.O + (size_t)head * n_q * kD, row0, n_q - row0, lane);
+        if (row0 + lr < n_q && h == 0) sd.LSE[(size_t)head * n_q + qrow] = (m_ref + log2f(l)) * kLn2;
+    }
+}
 // One body serves both launches: with STEPS the item, its buffers and its (trivial) pair ranges
 // come from the step descriptors, otherwise from the schedule tables.
 template <bool STEPS, typename Params>
@@ -68,8 +175,12 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
     const int32_t* rows = nullptr;    // row map of Q, O, LSE (steps over a subset of rows)
     const int32_t* row_lo = nullptr; const int32_t* row_hi = nullptr;
     if constexpr (STEPS) {
+        if (p.n_pack > 0 && item_id == p.n_items - 1) {
+            small_steps_pack(p, head, smem);
+            return;
+        }
         int si = 0;
-        while (si + 1 < p.n_steps && item_id >= p.step[si + 1].first_item) ++si;
+        while (si + 1 < p.n_tiled && item_id >= p.step[si + 1].first_item) ++si;
         const StepDesc& sd = p.step[si];
         const int li = item_id - sd.first_item;
         it.own_begin = li * 128;
@@ -290,9 +401,17 @@ hipError_t launch_fwd(const void* Q, const void* K, const void* V, void* O, floa
 hipError_t launch_fwd_steps(const StepLaunch& L, int n_heads, float sm_scale, int num_cus, hipStream_t stream) {
     if (L.n_steps < 1 || L.n_steps > kMaxSteps) return hipErrorInvalidValue;
     StepParams p;
+    // steps with items of their own first (in the given order), then the ones that share the pack
+    auto packed = [](const StepLaunch::Step& a) { return a.Lk <= kTile && a.rows == nullptr; };
+    int order[kMaxSteps], n = 0;
+    for (int i = 0; i < L.n_steps; ++i) if (!packed(L.step[i])) order[n++] = i;
+    p.n_tiled = n;
+    for (int i = 0; i < L.n_steps; ++i) if (packed(L.step[i])) order[n++] = i;
     int items = 0;
+    p.n_pack = 0;
     for (int i = 0; i < L.n_steps; ++i) {
-        const StepLaunch::Step& a = L.step[i];
+        const StepLaunch::Step& a = L.step[order[i]];
+        if (a.n_q < 1 || a.Lk < a.n_q) return hipErrorInvalidValue;
         StepDesc& d = p.step[i];
         d.Q = static_cast<const __bf16*>(a.Q);
         d.K = static_cast<const __bf16*>(a.K);
@@ -304,10 +423,16 @@ hipError_t launch_fwd_steps(const StepLaunch& L, int n_heads, float sm_scale, in
         d.q_stride = a.q_stride;
         d.Lk = a.Lk;
         d.first_item = items;
-        items += (a.n_q + 127) / 128;
+        if (i < p.n_tiled) {
+            items += (a.n_q + 127) / 128;
+        } else {
+            for (int blk = 0; 32 * blk < a.n_q; ++blk)         // at most two: n_q <= Lk <= 64
+                p.pack_unit[p.n_pack++] = 2 * i + blk;
+        }
     }
+    if (p.n_pack > 0) ++items;                                  // the pack is the launch's last item
     for (int i = L.n_steps; i < kMaxSteps; ++i) p.step[i] = p.step[0];
-    p.n_steps = L.n_steps;
+    for (int u = p.n_pack; u < kMaxPackUnits; ++u) p.pack_unit[u] = 0;
     p.n_items = items;
     p.n_heads = n_heads;
     p.tail_groups = tail_groups_for(num_cus, items);

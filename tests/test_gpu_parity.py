@@ -495,7 +495,10 @@ def test_counts_of_square_scales_give_the_same_bits_as_side_lengths():
     assert all(torch.equal(a, b) for a, b in zip(g1, g2))
 
 
-@pytest.mark.parametrize("n_prev,n_cur", [(0, 1), (1, 4), (25, 36), (100, 169), (169, 256), (7, 130), (300, 33)])
+@pytest.mark.parametrize("n_prev,n_cur", [(0, 1), (1, 4), (25, 36), (100, 169), (169, 256), (7, 130), (300, 33),
+                                          # steps of at most 64 keys take the kernel's wavefront-private path:
+                                          # one and two key blocks, one and two row blocks, ragged and full
+                                          (0, 32), (0, 33), (0, 64), (63, 1), (31, 33), (1, 63), (64, 1), (32, 33)])
 def test_inference_step_forward(n_prev, n_cur):
     # one KV-cache-free step (Sec. "Efficient Markovian Next-Scale Prediction"): n_cur queries
     # against the predecessor block + themselves
@@ -567,6 +570,27 @@ def test_more_steps_than_one_launch_holds():
         rO, rL = orc.attn_step_fwd(si.to_f64(Qs[i]), si.to_f64(KVs[i][0]), si.to_f64(KVs[i][1]), p)
         _compare(dict(O=Os[i], LSE=LSEs[i]), dict(O=rO.reshape(B * H, c, D), LSE=rL.reshape(B * H, c)),
                  _all_heads(B, H), "forty steps")
+
+
+def test_sixteen_small_steps_share_one_workgroup_per_head():
+    # every step has at most 64 keys, so the launch consists of the shared item alone and each
+    # wavefront works through several steps in turn; 15 heads leave one XCD's group ragged
+    B, H, D = 3, 5, 64
+    d = _dev()
+    shapes = [(0, 1), (1, 4), (4, 9), (9, 16), (16, 25), (25, 36), (0, 64), (31, 33), (0, 33), (63, 1), (30, 2),
+              (0, 32), (20, 40), (5, 5), (1, 63), (32, 32)]
+    Qs = [si.draw((B, H, c, D), seed=1200 + i, n_tensors=1)[0] for i, (p, c) in enumerate(shapes)]
+    KVs = [si.draw((B, H, p + c, D), seed=1250 + i, n_tensors=2) for i, (p, c) in enumerate(shapes)]
+    q = [t.to(d) for t in Qs]
+    for _ in range(2):     # the second call finds the LDS as the first one left it
+        Os, LSEs = hm.hmar_attn_steps_fwd(q, [kv[0].to(d) for kv in KVs], [kv[1].to(d) for kv in KVs],
+                                          [p for p, _ in shapes], Os=[_nan_like(t) for t in q],
+                                          LSEs=[_nan_stats(t.shape[:3], d) for t in q])
+        torch.cuda.synchronize()
+        for i, (p, c) in enumerate(shapes):
+            rO, rL = orc.attn_step_fwd(si.to_f64(Qs[i]), si.to_f64(KVs[i][0]), si.to_f64(KVs[i][1]), p)
+            _compare(dict(O=Os[i], LSE=LSEs[i]), dict(O=rO.reshape(B * H, c, D), LSE=rL.reshape(B * H, c)),
+                     _all_heads(B, H), "sixteen small steps")
 
 
 @pytest.mark.parametrize("n_prev,n_cur,n_rows", [(169, 256, 97), (100, 169, 169), (25, 36, 1), (0, 300, 131), (64, 100, 32)])
