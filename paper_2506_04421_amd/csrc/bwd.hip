@@ -44,7 +44,7 @@ __device__ __forceinline__ float neg_delta_of_row(const __bf16* o_row, const bf1
     float acc = 0.f;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        const bf16x8 ov = *reinterpret_cast<const bf16x8*>(o_row + 16 * t + 8 * h);
+        const bf16x8 ov = HMAR_ROW_LOAD(reinterpret_cast<const bf16x8*>(o_row + 16 * t + 8 * h));
         const bf16x8 gv = dob[t];
         // two products per instruction (v_dot2c_f32_bf16), fp32 accumulation
         acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(ov, ov, 0, 1), __builtin_shufflevector(gv, gv, 0, 1), acc, false);
@@ -92,8 +92,8 @@ __device__ __forceinline__ void dq_body(const BwdParams& p, const Item it, const
     bf16x8 q[4], dob[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        q[t] = *reinterpret_cast<const bf16x8*>(p.Q + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
-        dob[t] = *reinterpret_cast<const bf16x8*>(p.dO + head_in + (size_t)qrow * kD + 16 * t + 8 * h);
+        q[t] = HMAR_ROW_LOAD(reinterpret_cast<const bf16x8*>(p.Q + head_in + (size_t)qrow * kD + 16 * t + 8 * h));
+        dob[t] = HMAR_ROW_LOAD(reinterpret_cast<const bf16x8*>(p.dO + head_in + (size_t)qrow * kD + 16 * t + 8 * h));
     }
     float nl2, ndelta;
     if constexpr (OWN_STATS) {
@@ -173,7 +173,7 @@ __device__ __forceinline__ void dq_body(const BwdParams& p, const Item it, const
     }
 
     if (wave_active)
-        store_block_rows(smem_base + wave * kPatchBytes, dq, p.sm_scale, p.dQ + head_off, wq0, it.own_end - wq0, lane);
+        store_block_rows(smem_base + wave * kPatchBytes, dq, p.sm_scale, p.dQ + head_off, wq0, it.own_end - wq0, lane, nullptr, HMAR_NT_GRADS != 0);
 }
 
 __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(BwdParams p) {
@@ -236,8 +236,8 @@ __device__ __forceinline__ void dkdv_body(const BwdParams& p, const Item it, con
     bf16x8 kreg[4], vreg[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        kreg[t] = *reinterpret_cast<const bf16x8*>(p.K + head_in + (size_t)krow * kD + 16 * t + 8 * h);
-        vreg[t] = *reinterpret_cast<const bf16x8*>(p.V + head_in + (size_t)krow * kD + 16 * t + 8 * h);
+        kreg[t] = HMAR_ROW_LOAD(reinterpret_cast<const bf16x8*>(p.K + head_in + (size_t)krow * kD + 16 * t + 8 * h));
+        vreg[t] = HMAR_ROW_LOAD(reinterpret_cast<const bf16x8*>(p.V + head_in + (size_t)krow * kD + 16 * t + 8 * h));
     }
 
     f32x16 dk[2], dv[2];
@@ -345,8 +345,8 @@ __device__ __forceinline__ void dkdv_body(const BwdParams& p, const Item it, con
 
     if (wave_active) {
         const uint32_t patch = smem_base + wave * kPatchBytes;
-        store_block_rows(patch, dk, p.sm_scale, p.dK + head_off, wk0, it.own_end - wk0, lane);
-        store_block_rows(patch, dv, 1.0f, p.dV + head_off, wk0, it.own_end - wk0, lane);
+        store_block_rows(patch, dk, p.sm_scale, p.dK + head_off, wk0, it.own_end - wk0, lane, nullptr, HMAR_NT_GRADS != 0);
+        store_block_rows(patch, dv, 1.0f, p.dV + head_off, wk0, it.own_end - wk0, lane, nullptr, HMAR_NT_GRADS != 0);
     }
 }
 

@@ -68,8 +68,29 @@ struct alignas(16) Item { int32_t own_begin, own_end, other_begin, other_end; };
 //   HMAR_DKDV_PIPE / HMAR_DKDV_KEYS_PER_WAVE=16   a dK/dV kernel of tuning/dkdv_variants.inc instead: scores
 //                                                 formed one block ahead / 16 keys per wavefront on
 //                                                 16x16x32 MFMAs at four wavefronts per SIMD
+//   HMAR_NT_O / HMAR_NT_GRADS / HMAR_NT_ROW_LOADS = 0 | 1   cache policy of result stores and row loads (see below)
 //   HMAR_BWD_MERGED (+ HMAR_MERGED_*)             the backward of tuning/bwd_merged.inc instead: a row-statistics
 //                                                 kernel, then dQ and dK/dV items in one launch
+// Cache policy of the accesses no workgroup of the launch repeats (1 = non-temporal: the lines
+// are the first to leave the caches).  Result rows are written once and read by nobody in the
+// launch: storing them non-temporally keeps the streamed K/V (Q/dO) tiles, which other
+// workgroups of the head re-read, in the L2 longer: -1.5 % on a forward+backward step, measured on
+// the 256px and 512px training shapes.  Loading the once-read rows (a workgroup's own Q, dO, O
+// or K, V rows) non-temporally costs 4-9 % instead.
+#ifndef HMAR_NT_O
+#define HMAR_NT_O 1          // the forward's O rows
+#endif
+#ifndef HMAR_NT_GRADS
+#define HMAR_NT_GRADS 1      // dQ, dK, dV rows
+#endif
+#ifndef HMAR_NT_ROW_LOADS
+#define HMAR_NT_ROW_LOADS 0  // a workgroup's own rows
+#endif
+#if HMAR_NT_ROW_LOADS
+#define HMAR_ROW_LOAD(ptr) __builtin_nontemporal_load(ptr)
+#else
+#define HMAR_ROW_LOAD(ptr) (*(ptr))
+#endif
 #if defined(HMAR_TUNE_ALIAS_HEADS)
 #define HMAR_INPUT_HEAD(h) ((h) & 7)
 #else
@@ -284,13 +305,14 @@ __device__ __forceinline__ void mask_block(f32x16& s, int c0, int lim_lo, int li
 // 32 rows per instruction; instead it is transposed through a private LDS patch
 // (32 rows x kPatchPitch bytes) and leaves as full 128-byte rows, 8 rows per instruction.
 // `patch` is the LDS address of this wavefront's patch, `out` points at row 0 of the head, the
-// wavefront's rows are row0 .. row0 + nrows - 1 (at most 32; through row_map if given).  LDS operations of one wavefront execute in
+// wavefront's rows are row0 .. row0 + nrows - 1 (at most 32; through row_map if given); with
+// `streaming` the global stores are non-temporal.  LDS operations of one wavefront execute in
 // order, so no barrier is needed between the writes and the reads.
 constexpr int kPatchPitch = 144;                     // 128 + 16: keeps 16-byte alignment
 constexpr int kPatchBytes = 32 * kPatchPitch;        // per wavefront
 __device__ __forceinline__ void store_block_rows(uint32_t patch, const f32x16 (&acc)[2], float scale,
                                                  __bf16* out, int row0, int nrows, int lane,
-                                                 const int32_t* row_map = nullptr) {
+                                                 const int32_t* row_map = nullptr, bool streaming = false) {
     typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
     typedef const __attribute__((address_space(3))) u32x4 lds_u32x4;
     const int lr = lane & 31, h = lane >> 5;
@@ -308,7 +330,8 @@ __device__ __forceinline__ void store_block_rows(uint32_t patch, const f32x16 (&
         const u32x4 v = *(lds_u32x4*)(patch + row * kPatchPitch + chunk * 16);
         if (row < nrows) {
             const int r = row_map ? row_map[row0 + row] : row0 + row;
-            *reinterpret_cast<u32x4*>(out + (size_t)r * kD + chunk * 8) = v;
+            if (streaming) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (size_t)r * kD + chunk * 8));
+            else *reinterpret_cast<u32x4*>(out + (size_t)r * kD + chunk * 8) = v;
         }
     }
 }

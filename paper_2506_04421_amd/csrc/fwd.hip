@@ -237,7 +237,7 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
     bf16x8 q[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
-        q[t] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow_mem * kD + 16 * t + 8 * h);
+        q[t] = HMAR_ROW_LOAD(reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow_mem * kD + 16 * t + 8 * h));
 
     f32x16 o[2];
 #pragma unroll
@@ -331,7 +331,7 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
     // through which the output block is turned into full rows
     if (wave_active) {
         const float l = half_sum(lsum);
-        store_block_rows(smem_base + wave * kPatchBytes, o, 1.0f / l, Oh, wq0, it.own_end - wq0, lane, rows);
+        store_block_rows(smem_base + wave * kPatchBytes, o, 1.0f / l, Oh, wq0, it.own_end - wq0, lane, rows, HMAR_NT_O != 0);
         if (row_valid && h == 0) LSEh[qrow_mem] = (m_ref + log2f(l)) * kLn2;
     }
 }

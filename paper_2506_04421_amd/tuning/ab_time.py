@@ -7,7 +7,8 @@
 `main` is libhmar_attn.so, any other name libhmar_attn_<name>.so (see build.py).  Every build
 runs forward and backward on the same three rotating buffer sets (larger than the last-level
 cache), in rounds that alternate between the builds so that clock and temperature drift hit all
-alike; the medians over the rounds are printed, with the first build as the reference.  Before
+alike; the medians over the rounds are printed (forward, backward, and the two back to back on
+the same buffers), with the first build as the reference.  Before
 the timing, the outputs of every build are compared with the first one's (variants that skip
 arithmetic or alias inputs differ by design: the comparison is printed, not asserted).
 """
@@ -100,11 +101,15 @@ def main() -> int:
         for s in sets:
             fwd(libs[names[0]], s)
         torch.cuda.synchronize()
+    def step(lib, s):
+        fwd(lib, s)
+        bwd(lib, s)
+
     rounds, inner = 12, 9
-    res = {n: {"fwd": [], "bwd": []} for n in names}
+    res = {n: {"fwd": [], "bwd": [], "step": []} for n in names}
     for _ in range(rounds):
         for n in names:
-            for what, fn in (("fwd", fwd), ("bwd", bwd)):
+            for what, fn in (("fwd", fwd), ("bwd", bwd), ("step", step)):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
                 for i in range(inner):
@@ -114,11 +119,13 @@ def main() -> int:
                 res[n][what].append(e0.elapsed_time(e1) / inner * 1000)
     f0 = statistics.median(res[names[0]]["fwd"])
     b0 = statistics.median(res[names[0]]["bwd"])
+    s0 = statistics.median(res[names[0]]["step"])
     for n in names:
         f = statistics.median(res[n]["fwd"])
         b = statistics.median(res[n]["bwd"])
+        st = statistics.median(res[n]["step"])
         print(f"{w.name} {n:14s} fwd {f:7.1f} us ({(f / f0 - 1) * 100:+5.1f} %)  bwd {b:7.1f} us "
-              f"({(b / b0 - 1) * 100:+5.1f} %)", flush=True)
+              f"({(b / b0 - 1) * 100:+5.1f} %)  fwd+bwd {st:7.1f} us ({(st / s0 - 1) * 100:+5.1f} %)", flush=True)
     return 0
 
 
