@@ -107,8 +107,14 @@ def other_workloads(hm, si, torch, dev, reps: int = 24):
     through enough buffer sets that a launch never finds its operands in the 256 MB last-level
     cache from the launch before (working sets: 180 MB to 670 MB per set)."""
     def gpu_ms(fn, n=reps):
-        for i in range(3):
+        # the same untimed load first, so that the clocks have settled (see SPIN_UP_S)
+        t0, i = time.perf_counter(), 0
+        while time.perf_counter() - t0 < 0.08:
             fn(i)
+            i += 1
+            if i % 8 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for i in range(n):
