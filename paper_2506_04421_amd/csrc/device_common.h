@@ -68,6 +68,7 @@ struct alignas(16) Item { int32_t own_begin, own_end, other_begin, other_end; };
 //   HMAR_DKDV_PIPE / HMAR_DKDV_KEYS_PER_WAVE=16   a dK/dV kernel of tuning/dkdv_variants.inc instead: scores
 //                                                 formed one block ahead / 16 keys per wavefront on
 //                                                 16x16x32 MFMAs at four wavefronts per SIMD
+//   HMAR_FWD_STAGES = 2 | 3 | 4                   stages of the forward's K/V ring (csrc/fwd.hip)
 //   HMAR_NT_O / HMAR_NT_GRADS / HMAR_NT_ROW_LOADS = 0 | 1   cache policy of result stores and row loads (see below)
 //   HMAR_BWD_MERGED (+ HMAR_MERGED_*)             the backward of tuning/bwd_merged.inc instead: a row-statistics
 //                                                 kernel, then dQ and dK/dV items in one launch

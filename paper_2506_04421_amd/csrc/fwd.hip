@@ -63,6 +63,13 @@ constexpr float kRescaleThreshold = 8.0f;
 #ifndef HMAR_FWD_MIN_WAVES
 #define HMAR_FWD_MIN_WAVES 4
 #endif
+// Stages of the K/V ring (each 16 KB); the loads run HMAR_FWD_STAGES - 1 tiles ahead.  Two is what
+// ships (see device_common.h); 3 and 4 exist for the measurement that decided it.
+#ifndef HMAR_FWD_STAGES
+#define HMAR_FWD_STAGES 2
+#endif
+constexpr int kFwdStages = HMAR_FWD_STAGES;
+static_assert(kFwdStages >= 2 && kFwdStages <= 4, "ring depth");
 
 // The pack item of a steps launch: inference steps with at most 64 keys.  A wavefront takes the
 // units u = wave, wave + 4, ... and computes each alone, without the workgroup: the unit's 32 query
@@ -216,6 +223,9 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
         dma_tile(Vh, k_begin + ti * kTile, kmax, stage + kTileBytes, lo_, lane, wave);
     };
     issue(0, 0);
+#pragma unroll
+    for (int d = 1; d < kFwdStages - 1; ++d)
+        if (d < ntiles) issue(d, d);
 
     const int wq0 = it.own_begin + wave * kRowsPerWave;
     const bool wave_active = wq0 < it.own_end;               // uniform over the wavefront
@@ -259,8 +269,9 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
     auto tile_step = [&](const int ti, auto stage_c) {
         constexpr int ST = decltype(stage_c)::value;
         const int kt = k_begin + ti * kTile;
-        // the next tile goes into the other stage, which every wavefront left at the last barrier
-        if (ti + 1 < ntiles) issue(ti + 1, ST ^ 1);
+        // the tile requested now goes into the stage that every wavefront left at the last barrier
+        const bool ahead = ti + kFwdStages - 1 < ntiles;
+        if (ahead) issue(ti + kFwdStages - 1, (ST + kFwdStages - 1) % kFwdStages);
 #ifdef HMAR_TUNE_NO_COMPUTE_FWD
         if (false) {
 #else
@@ -319,12 +330,23 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
                     o[mb] = mfma32(lds_a_tr(Vt, lo_, mb, tp), pb, o[mb]);
             }
         }
-        HMAR_WAIT_DMA_AND_BARRIER(0);     // the tile requested above has landed and this one is free
+        // the next tile has landed (4 loads per lane and tile: the younger tiles may still be in
+        // flight) and this one is free
+        if (kFwdStages > 2 && ahead) { HMAR_WAIT_DMA_AND_BARRIER(4 * (kFwdStages - 2)); }
+        else                         { HMAR_WAIT_DMA_AND_BARRIER(0); }
     };
-    for (int ti = 0; ti < ntiles; ti += 2) {
+    for (int ti = 0; ti < ntiles; ti += kFwdStages) {
         tile_step(ti, std::integral_constant<int, 0>{});
         if (ti + 1 >= ntiles) break;
         tile_step(ti + 1, std::integral_constant<int, 1>{});
+        if constexpr (kFwdStages > 2) {
+            if (ti + 2 >= ntiles) break;
+            tile_step(ti + 2, std::integral_constant<int, 2>{});
+        }
+        if constexpr (kFwdStages > 3) {
+            if (ti + 3 >= ntiles) break;
+            tile_step(ti + 3, std::integral_constant<int, 3>{});
+        }
     }
 
     // every wavefront has passed the last barrier: the ring is free and serves as the patch
@@ -337,8 +359,8 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
 }
 
 __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(FwdParams p) {
-    // ring of 2 stages, each a K tile followed by a V tile
-    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+    // ring of stages, each a K tile followed by a V tile
+    __shared__ __attribute__((aligned(1024))) char smem[kFwdStages * 2 * kTileBytes];
 #ifdef HMAR_TUNE_LDS_PAD_FWD
     HMAR_TUNE_LDS_PAD(HMAR_TUNE_LDS_PAD_FWD)
 #endif
@@ -346,7 +368,7 @@ __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_kernel(
 }
 
 __global__ __launch_bounds__(kThreads, HMAR_FWD_MIN_WAVES) void hmar_fwd_steps_kernel(StepParams p) {
-    __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+    __shared__ __attribute__((aligned(1024))) char smem[kFwdStages * 2 * kTileBytes];
     fwd_body<true>(p, smem);
 }
 
