@@ -15,6 +15,7 @@
 // workgroups: results are deterministic and nothing needs zero-initialising.  Streamed
 // tiles are row-major in LDS and serve both as row-wise operands (S, dP) and, through the
 // LDS transpose load, as transposed operands (dQ, dK, dV).
+#include <algorithm>
 #include <type_traits>
 
 #include "device_common.h"
@@ -194,6 +195,84 @@ __global__ __launch_bounds__(kThreads, HMAR_DQ_MIN_WAVES) void hmar_dq_kernel(Bw
 #ifndef HMAR_DKDV_MIN_WAVES
 #define HMAR_DKDV_MIN_WAVES 2
 #endif
+// One tile of the dK/dV computation: the wavefront's 32 keys (rows kreg, vreg) against the 64
+// query rows of the tile at LDS addresses Qt (Q) and Gt (dO), whose statistics are at nl2_t and
+// delta_t.  lim_lo, lim_hi: the lane's key pairs with tile rows [lim_lo + 4h, lim_hi + 4h).
+__device__ __forceinline__ void dkdv_tile(uint32_t Qt, uint32_t Gt, uint32_t nl2_t, uint32_t delta_t,
+                                          const bf16x8 (&kreg)[4], const bf16x8 (&vreg)[4], f32x16 (&dk)[2], f32x16 (&dv)[2],
+                                          int lim_lo, int lim_hi, bool need_lo, bool need_hi, float c,
+                                          const LaneOffsets& lo_) {
+    // Operands are fetched from LDS in batches ahead of the contractions that use them
+    // (the scheduling barriers keep the compiler from sinking each read next to its use,
+    // which would expose the LDS latency once per matrix instruction).  The score and dP
+    // contractions of both 32-query blocks are issued first, so that the matrix pipe works
+    // on the second block while the vector units form the first block's probabilities.
+    f32x16 s[2], dp[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        bf16x8 aq[4], ag[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            aq[t] = lds_a_row(Qt, lo_, qb, t);
+            ag[t] = lds_a_row(Gt, lo_, qb, t);
+        }
+        // statistics of the block's query rows 32qb + 8j + 4h + r (register 4j + r):
+        // -Delta seeds the dP accumulator, so dP - Delta costs no vector instruction
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 d4 = *(lds_f32x4*)(delta_t + (32 * qb + 8 * j) * 4);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { s[qb][4 * j + r] = 0.f; dp[qb][4 * j + r] = d4[r]; }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            s[qb] = mfma32(aq[t], kreg[t], s[qb]);
+            dp[qb] = mfma32(ag[t], vreg[t], dp[qb]);
+        }
+    }
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        // transposed operands of the second pair of contractions and the row statistics,
+        // requested before the exponentials so that their latency hides behind them
+        bf16x8 tg[2][2], tq[2][2];
+        f32x4 l4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) l4[j] = *(lds_f32x4*)(nl2_t + (32 * qb + 8 * j) * 4);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+                tg[sub][mb] = lds_a_tr(Gt, lo_, mb, 2 * qb + sub);
+                tq[sub][mb] = lds_a_tr(Qt, lo_, mb, 2 * qb + sub);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        mask_block(s[qb], 32 * qb, lim_lo, lim_hi, need_lo, need_hi);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = 4 * j + r;
+                const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][i], c, l4[j][r]));
+                s[qb][i] = pv;
+                dp[qb][i] = pv * dp[qb][i];
+            }
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int e0 = 8 * sub;
+            const bf16x8 pb = pack8(s[qb][e0 + 0], s[qb][e0 + 1], s[qb][e0 + 2], s[qb][e0 + 3],
+                                    s[qb][e0 + 4], s[qb][e0 + 5], s[qb][e0 + 6], s[qb][e0 + 7]);
+            const bf16x8 dsb = pack8(dp[qb][e0 + 0], dp[qb][e0 + 1], dp[qb][e0 + 2], dp[qb][e0 + 3],
+                                     dp[qb][e0 + 4], dp[qb][e0 + 5], dp[qb][e0 + 6], dp[qb][e0 + 7]);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+                dv[mb] = mfma32(tg[sub][mb], pb, dv[mb]);
+                dk[mb] = mfma32(tq[sub][mb], dsb, dk[mb]);
+            }
+        }
+    }
+}
+
 // The work of one dK/dV item.  smem: ring of 2 stages, each a Q tile followed by a dO tile;
 // nl2_s, delta_s: the per-row statistics of the two stages.
 __device__ __forceinline__ void dkdv_body(const BwdParams& p, const Item it, const int32_t* row_lo, const int32_t* row_hi,
@@ -260,80 +339,10 @@ __device__ __forceinline__ void dkdv_body(const BwdParams& p, const Item it, con
         if (wave_active && qt < whi && qt + kTile > wlo) {
 #endif
             const uint32_t Qt = smem_base + ST * (2 * kTileBytes);
-            const uint32_t Gt = Qt + kTileBytes;
             const uint32_t nl2_t = nl2_base + ST * (kTile * 4) + 16 * h;
             const uint32_t delta_t = delta_base + ST * (kTile * 4) + 16 * h;
-            const bool need_lo = qt < full_lo, need_hi = qt + kTile > full_hi;
-            const int lim_lo = lo - qt - 4 * h, lim_hi = hi - qt - 4 * h;
-            // Operands are fetched from LDS in batches ahead of the contractions that use them
-            // (the scheduling barriers keep the compiler from sinking each read next to its use,
-            // which would expose the LDS latency once per matrix instruction).  The score and dP
-            // contractions of both 32-query blocks are issued first, so that the matrix pipe works
-            // on the second block while the vector units form the first block's probabilities.
-            f32x16 s[2], dp[2];
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                bf16x8 aq[4], ag[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    aq[t] = lds_a_row(Qt, lo_, qb, t);
-                    ag[t] = lds_a_row(Gt, lo_, qb, t);
-                }
-                // statistics of the block's query rows 32qb + 8j + 4h + r (register 4j + r):
-                // -Delta seeds the dP accumulator, so dP - Delta costs no vector instruction
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const f32x4 d4 = *(lds_f32x4*)(delta_t + (32 * qb + 8 * j) * 4);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) { s[qb][4 * j + r] = 0.f; dp[qb][4 * j + r] = d4[r]; }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    s[qb] = mfma32(aq[t], kreg[t], s[qb]);
-                    dp[qb] = mfma32(ag[t], vreg[t], dp[qb]);
-                }
-            }
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                // transposed operands of the second pair of contractions and the row statistics,
-                // requested before the exponentials so that their latency hides behind them
-                bf16x8 tg[2][2], tq[2][2];
-                f32x4 l4[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) l4[j] = *(lds_f32x4*)(nl2_t + (32 * qb + 8 * j) * 4);
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb) {
-                        tg[sub][mb] = lds_a_tr(Gt, lo_, mb, 2 * qb + sub);
-                        tq[sub][mb] = lds_a_tr(Qt, lo_, mb, 2 * qb + sub);
-                    }
-                __builtin_amdgcn_sched_barrier(0);
-                mask_block(s[qb], 32 * qb, lim_lo, lim_hi, need_lo, need_hi);
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int i = 4 * j + r;
-                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][i], p.c, l4[j][r]));
-                        s[qb][i] = pv;
-                        dp[qb][i] = pv * dp[qb][i];
-                    }
-#pragma unroll
-                for (int sub = 0; sub < 2; ++sub) {
-                    const int e0 = 8 * sub;
-                    const bf16x8 pb = pack8(s[qb][e0 + 0], s[qb][e0 + 1], s[qb][e0 + 2], s[qb][e0 + 3],
-                                            s[qb][e0 + 4], s[qb][e0 + 5], s[qb][e0 + 6], s[qb][e0 + 7]);
-                    const bf16x8 dsb = pack8(dp[qb][e0 + 0], dp[qb][e0 + 1], dp[qb][e0 + 2], dp[qb][e0 + 3],
-                                             dp[qb][e0 + 4], dp[qb][e0 + 5], dp[qb][e0 + 6], dp[qb][e0 + 7]);
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb) {
-                        dv[mb] = mfma32(tg[sub][mb], pb, dv[mb]);
-                        dk[mb] = mfma32(tq[sub][mb], dsb, dk[mb]);
-                    }
-                }
-            }
+            dkdv_tile(Qt, Qt + kTileBytes, nl2_t, delta_t, kreg, vreg, dk, dv, lo - qt - 4 * h, hi - qt - 4 * h,
+                      qt < full_lo, qt + kTile > full_hi, p.c, lo_);
         }
         HMAR_WAIT_DMA_AND_BARRIER(0);
     };
@@ -364,6 +373,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(HMAR_D
 
 #if defined(HMAR_BWD_MERGED)
 #include "../tuning/bwd_merged.inc"
+#endif
+#if defined(HMAR_DKDV_PERSIST)
+#include "../tuning/dkdv_persist.inc"
 #endif
 
 #if defined(HMAR_DKDV_PIPE) || (defined(HMAR_DKDV_KEYS_PER_WAVE) && HMAR_DKDV_KEYS_PER_WAVE == 16)
@@ -430,6 +442,12 @@ hipError_t launch_bwd(const void* Q, const void* K, const void* V, const void* O
         if (dir == 1) hipLaunchKernelGGL(hmar_dkdv16_kernel, dim3((unsigned)groups), dim3(kThreads16), 0, stream, p);
 #elif defined(HMAR_DKDV_PIPE)
         if (dir == 1) hipLaunchKernelGGL(hmar_dkdv_pipe_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
+#elif defined(HMAR_DKDV_PERSIST)
+        if (dir == 1) {
+            const long long resident = 2LL * s.num_cus / 8 * 8;       // two workgroups per CU, a multiple of 8
+            hipLaunchKernelGGL(hmar_dkdv_persist_kernel, dim3((unsigned)std::min(groups, resident)), dim3(kThreads), 0, stream,
+                               p, (int)groups);
+        }
 #else
         if (dir == 1) hipLaunchKernelGGL(hmar_dkdv_kernel, dim3((unsigned)groups), dim3(kThreads), 0, stream, p);
 #endif

@@ -70,6 +70,9 @@ struct alignas(16) Item { int32_t own_begin, own_end, other_begin, other_end; };
 //                                                 16x16x32 MFMAs at four wavefronts per SIMD
 //   HMAR_FWD_STAGES = 2 | 3 | 4                   stages of the forward's K/V ring (csrc/fwd.hip)
 //   HMAR_NT_O / HMAR_NT_GRADS / HMAR_NT_ROW_LOADS = 0 | 1   cache policy of result stores and row loads (see below)
+//   HMAR_DKDV_PERSIST                             the dK/dV kernel of tuning/dkdv_persist.inc instead: two resident
+//                                                 workgroups per CU walk the (head, item) units, the next unit's
+//                                                 first tile and key rows requested before the current one's results leave
 //   HMAR_BWD_MERGED (+ HMAR_MERGED_*)             the backward of tuning/bwd_merged.inc instead: a row-statistics
 //                                                 kernel, then dQ and dK/dV items in one launch
 // Cache policy of the accesses no workgroup of the launch repeats (1 = non-temporal: the lines
@@ -117,9 +120,8 @@ typedef const __attribute__((address_space(1))) void global_void;
 //  - With `reverse` the groups are walked from the last to the first: a kernel that follows
 //    another one over the same tensors then starts on the heads that kernel touched last,
 //    which are the ones still in the last-level cache.
-__device__ __forceinline__ bool map_workgroup(int n_items, int n_heads, int tail_groups, int* head, int* item,
-                                              bool reverse = false) {
-    const int wg = blockIdx.x;
+__device__ __forceinline__ bool map_unit(int wg, int n_items, int n_heads, int tail_groups, int* head, int* item,
+                                         bool reverse = false) {
     const int xcd = wg & 7;
     const int slot = wg >> 3;
     const int n_groups = (n_heads + 7) / 8;
@@ -132,6 +134,10 @@ __device__ __forceinline__ bool map_workgroup(int n_items, int n_heads, int tail
     *head = group * 8 + xcd;
     *item = it;
     return *head < n_heads;
+}
+__device__ __forceinline__ bool map_workgroup(int n_items, int n_heads, int tail_groups, int* head, int* item,
+                                              bool reverse = false) {
+    return map_unit(blockIdx.x, n_items, n_heads, tail_groups, head, item, reverse);
 }
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
