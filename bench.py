@@ -130,7 +130,8 @@ def other_workloads(hm, si, torch, dev, reps: int = 24):
     def rnd(shape):
         return torch.randn(shape, device=dev, generator=g).to(torch.bfloat16)
 
-    for name, mask in (("256px_b16_h16", 0), ("256px_b32_h30", 0), ("512px_b8_h24", 0), ("256px_b32_h24", 1)):
+    for name, mask in (("256px_b16_h16", 0), ("256px_b32_h30", 0), ("512px_b8_h24", 0), ("256px_b32_h24", 1),
+                       ("512px_b8_h24", 1), ("large_synthetic_b2_h24", 0), ("large_synthetic_b2_h24", 1)):
         w = si.WORKLOADS[name]
         shape = (w.B, w.H, w.L, w.D)
         one_set = 8 * w.B * w.H * w.L * w.D * 2

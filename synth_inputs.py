@@ -36,6 +36,10 @@ class Workload:
 SIDES_TINY = (1, 2, 3, 4)
 SIDES_256 = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
 SIDES_512 = (1, 2, 3, 4, 6, 9, 13, 18, 24, 32)
+# SYNTHETIC: the paper times its kernel at 1024px too but never lists that schedule; this one only
+# continues the 512px schedule by two scales (L = 8640) to show how the path scales.  Not a
+# parity target of the paper's.
+SIDES_LARGE_SYNTHETIC = SIDES_512 + (48, 64)
 
 WORKLOADS = {
     "tiny": Workload("tiny", SIDES_TINY, 2, 2, 64, 0),
@@ -43,6 +47,7 @@ WORKLOADS = {
     "256px_b32_h24": Workload("256px_b32_h24", SIDES_256, 32, 24, 64, 2),
     "256px_b32_h30": Workload("256px_b32_h30", SIDES_256, 32, 30, 64, 3),
     "512px_b8_h24": Workload("512px_b8_h24", SIDES_512, 8, 24, 64, 4),
+    "large_synthetic_b2_h24": Workload("large_synthetic_b2_h24", SIDES_LARGE_SYNTHETIC, 2, 24, 64, 5),
 }
 
 

@@ -229,6 +229,21 @@ def test_full_size_workloads_every_head(name):
     assert torch.equal(res["O"][:, :, 0, :].cpu(), V[:, :, 0, :])
 
 
+def test_synthetic_larger_schedule_on_sampled_heads():
+    # the synthetic continuation of the 512px schedule that the benchmark times for context
+    # (L = 8640, 48 heads): two heads against the oracle (its dense fp64 matrices are 0.6 GB
+    # each at this length), every head finite and its first row exact
+    w = si.WORKLOADS["large_synthetic_b2_h24"]
+    Q, K, V, dO = si.make_inputs(w)
+    sm = 1.0 / math.sqrt(w.D)
+    res = _gpu_run(Q, K, V, dO, w.sides, sm)
+    heads = [(0, 3), (1, 20)]
+    _compare(res, _oracle_heads(Q, K, V, dO, w.sides, sm, heads), heads, w.name)
+    for t in res.values():
+        assert torch.isfinite(t).all()
+    assert torch.equal(res["O"][:, :, 0, :].cpu(), V[:, :, 0, :])
+
+
 def test_large_scores_exercise_the_running_maximum():
     # scores of magnitude ~30-40: the running reference maximum must be raised mid-window
     sides = si.SIDES_256
