@@ -17,12 +17,16 @@ struct DeviceSchedule {
 };
 
 // Number of head groups (8 heads each) in the batch that ends a launch item by item (see
-// map_workgroup): about as many (head, item) units as one XCD keeps resident at four
-// workgroups per CU.  Measured on the 256px and 512px training shapes: batches between 0.75
-// and 1.25 times that shorten the launches by 2-4 % and 5-6 %; batching the whole launch
-// this way instead of its end only loses more in L2 locality than it gains.
+// map_workgroup): about twice as many (head, item) units as one XCD keeps resident at four
+// workgroups per CU.  Measured on the 256px and 512px training shapes (forward+backward step):
+// without the batch +1.5 % and +3.8 %; half the size 0 and +1.7 %; twice the size +1.7 % and +1 %;
+// batching the whole launch this way instead of its end only loses more in L2 locality than it
+// gains.
+#ifndef HMAR_TUNE_TAIL_PERCENT
+#define HMAR_TUNE_TAIL_PERCENT 100     // measurement builds: size of the batch relative to the shipped one
+#endif
 inline int tail_groups_for(int num_cus, int n_items) {
-    const int g = ((num_cus / 8) * 4) / (n_items > 0 ? n_items : 1);
+    const int g = ((num_cus / 8) * 8) * HMAR_TUNE_TAIL_PERCENT / 100 / (n_items > 0 ? n_items : 1);
     return g < 1 ? 1 : g;
 }
 
