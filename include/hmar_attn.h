@@ -167,7 +167,11 @@ hmar_status hmar_attn_bwd_masked(const void* Q, const void* K, const void* V, co
  * that overlap in time on one GPU (two streams, two threads) race; calls on one stream, or
  * ordered by events, are safe.  When the schedule differs from the previous call's on that GPU
  * its tables (a few KB) are first written to the array by small kernels on `stream`, their
- * contents carried in the kernel arguments.  Markovian mask, scales given by side lengths. */
+ * contents carried in the kernel arguments.  A call made while `stream` is being captured into
+ * a graph always records those writes, so that every replay brings its own tables; from then on
+ * calls outside graphs write theirs every time as well (a replay may have changed the array).
+ * The first call on a GPU looks up the array's address and must be made outside a capture.
+ * Markovian mask, scales given by side lengths. */
 #define HMAR_NOALLOC_MAX_ROWS (1 << 20)
 #define HMAR_NOALLOC_MAX_SEQ_LEN 8192
 hmar_status hmar_attn_bwd_noalloc(const void* Q, const void* K, const void* V, const void* O,

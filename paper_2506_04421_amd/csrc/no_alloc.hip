@@ -33,6 +33,8 @@ constexpr int kMaxDevices = 64;
 struct DeviceState {
     unsigned char* ptr = nullptr;          // this device's copy of `scratch`
     bool have_tables = false;              // the array holds the tables of (kind, sizes)
+    bool graph_seen = false;               // some call was recorded into a graph: its replays rewrite the
+                                           // tables at times this code cannot know
     int32_t kind = 0;
     std::vector<int32_t> sizes;
     hmar::DeviceSchedule dev{};
@@ -68,6 +70,12 @@ extern "C" hmar_status hmar_attn_bwd_noalloc(const void* Q, const void* K, const
     const int cus = hmar::device_cus(dev);
     if (cus < 1) return HMAR_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    // A call that is being recorded into a graph must carry its tables with it: the graph is
+    // replayed later, when the array may hold another schedule's.
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capture) != hipSuccess) return HMAR_ERR_HIP;
+    if (capture == hipStreamCaptureStatusInvalidated) return HMAR_ERR_HIP;
+    const bool capturing = capture == hipStreamCaptureStatusActive;
 
     hmar::DeviceSchedule ds;
     unsigned char* base = nullptr;
@@ -81,7 +89,10 @@ extern "C" hmar_status hmar_attn_bwd_noalloc(const void* Q, const void* K, const
             state.ptr = static_cast<unsigned char*>(p);
         }
         base = state.ptr;
-        const bool same = state.have_tables && state.kind == pb.mask_kind && (int32_t)state.sizes.size() == num_scales &&
+        if (capturing) state.graph_seen = true;
+        // once graphs exist the array's tables are only known to be this call's if this call writes them
+        const bool same = !state.graph_seen && state.have_tables && state.kind == pb.mask_kind &&
+                          (int32_t)state.sizes.size() == num_scales &&
                           std::memcmp(state.sizes.data(), side_lens, sizeof(int32_t) * (size_t)num_scales) == 0;
         if (!same) {
             hmar::Schedule host;
