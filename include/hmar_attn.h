@@ -119,7 +119,9 @@ hmar_status hmar_attn_steps_fwd(const void* const* Q, const void* const* K, cons
  * are not listed are left untouched; K and V as in hmar_attn_step_fwd (the predecessor block's
  * n_prev rows are the same in every pass of a scale and stay where they are).
  * rows: DEVICE pointer, int32, n_rows distinct values in [0, n_cur), 4-byte aligned, shared by
- * all heads.  1 <= n_rows <= n_cur.  Allocates nothing. */
+ * all heads.  1 <= n_rows <= n_cur.  The values are device data and not checked: one outside
+ * the range is clamped into it (no access leaves the buffers; what is written for such an
+ * entry is unspecified).  Allocates nothing. */
 hmar_status hmar_attn_step_fwd_rows(const void* Q, const void* K, const void* V, void* O, float* LSE,
                                     const int32_t* rows, int32_t n_rows,
                                     int32_t n_prev, int32_t n_cur, int32_t B, int32_t H, int32_t D,

@@ -312,14 +312,16 @@ __device__ __forceinline__ void mask_block(f32x16& s, int c0, int lim_lo, int li
 // 32 rows per instruction; instead it is transposed through a private LDS patch
 // (32 rows x kPatchPitch bytes) and leaves as full 128-byte rows, 8 rows per instruction.
 // `patch` is the LDS address of this wavefront's patch, `out` points at row 0 of the head, the
-// wavefront's rows are row0 .. row0 + nrows - 1 (at most 32; through row_map if given); with
+// wavefront's rows are row0 .. row0 + nrows - 1 (at most 32; through row_map if given, its
+// entries clamped to [0, map_rows) so that a bad index cannot leave the buffer); with
 // `streaming` the global stores are non-temporal.  LDS operations of one wavefront execute in
 // order, so no barrier is needed between the writes and the reads.
 constexpr int kPatchPitch = 144;                     // 128 + 16: keeps 16-byte alignment
 constexpr int kPatchBytes = 32 * kPatchPitch;        // per wavefront
 __device__ __forceinline__ void store_block_rows(uint32_t patch, const f32x16 (&acc)[2], float scale,
                                                  __bf16* out, int row0, int nrows, int lane,
-                                                 const int32_t* row_map = nullptr, bool streaming = false) {
+                                                 const int32_t* row_map = nullptr, bool streaming = false,
+                                                 int map_rows = 1) {
     typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
     typedef const __attribute__((address_space(3))) u32x4 lds_u32x4;
     const int lr = lane & 31, h = lane >> 5;
@@ -336,7 +338,7 @@ __device__ __forceinline__ void store_block_rows(uint32_t patch, const f32x16 (&
         const int row = 8 * i + (lane >> 3), chunk = lane & 7;
         const u32x4 v = *(lds_u32x4*)(patch + row * kPatchPitch + chunk * 16);
         if (row < nrows) {
-            const int r = row_map ? row_map[row0 + row] : row0 + row;
+            const int r = row_map ? min(max(row_map[row0 + row], 0), map_rows - 1) : row0 + row;
             if (streaming) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + (size_t)r * kD + chunk * 8));
             else *reinterpret_cast<u32x4*>(out + (size_t)r * kD + chunk * 8) = v;
         }

@@ -180,6 +180,7 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
     const __bf16* Qh; const __bf16* Kh; const __bf16* Vh;
     __bf16* Oh; float* LSEh;
     const int32_t* rows = nullptr;    // row map of Q, O, LSE (steps over a subset of rows)
+    int q_stride_rows = 0;            // rows per head of those buffers (steps)
     const int32_t* row_lo = nullptr; const int32_t* row_hi = nullptr;
     if constexpr (STEPS) {
         if (p.n_pack > 0 && item_id == p.n_items - 1) {
@@ -199,6 +200,7 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
         Kh = sd.K + (size_t)HMAR_INPUT_HEAD(head) * sd.Lk * kD;
         Vh = sd.V + (size_t)HMAR_INPUT_HEAD(head) * sd.Lk * kD;
         rows = sd.rows;
+        q_stride_rows = sd.q_stride;
     } else {
         it = p.items[item_id];
         const size_t q_off = (size_t)head * p.L, q_in = (size_t)HMAR_INPUT_HEAD(head) * p.L;
@@ -243,7 +245,10 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
         full_lo = row_lo[rlast]; full_hi = row_hi[rfirst];  // what every one of its rows pairs with
     }
 
-    const int qrow_mem = rows ? rows[qrow] : qrow;
+    // a listed row outside the buffer is clamped into it: wrong input must not become a wild access
+    int q_rows_per_head = 0;
+    if constexpr (STEPS) q_rows_per_head = q_stride_rows;
+    const int qrow_mem = rows ? min(max(rows[qrow], 0), q_rows_per_head - 1) : qrow;
     bf16x8 q[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -353,7 +358,8 @@ __device__ __forceinline__ void fwd_body(const Params& p, char* smem) {
     // through which the output block is turned into full rows
     if (wave_active) {
         const float l = half_sum(lsum);
-        store_block_rows(smem_base + wave * kPatchBytes, o, 1.0f / l, Oh, wq0, it.own_end - wq0, lane, rows, HMAR_NT_O != 0);
+        store_block_rows(smem_base + wave * kPatchBytes, o, 1.0f / l, Oh, wq0, it.own_end - wq0, lane, rows, HMAR_NT_O != 0,
+                         q_rows_per_head);
         if (row_valid && h == 0) LSEh[qrow_mem] = (m_ref + log2f(l)) * kLn2;
     }
 }
